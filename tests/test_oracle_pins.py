@@ -1,0 +1,366 @@
+"""Pins for the CPU oracle: every function is checked against something other than itself.
+
+Hand-derived rationals, closed forms, library routines on special cases, brute force on
+tiny inputs and the invariants the paper states (Prop. 1, Thm. 2, budgets summing to B_total).
+"""
+import itertools
+import json
+import math
+import os
+import statistics
+from fractions import Fraction
+
+import numpy as np
+import pytest
+import scipy.special
+import torch
+
+from oracle import cake_oracle as co
+from synth import CONFIGS, make_layer
+
+GOLDEN = os.path.join(os.path.dirname(__file__), "golden", "rational_example.json")
+
+
+def _f(s):
+    return float(Fraction(s))
+
+
+# ---------------------------------------------------------------- worked rational example
+def _example_inputs(heads):
+    g = json.load(open(GOLDEN))
+    k = np.log(np.array(g["keys_exp"], dtype=np.float64)).reshape(1, 4, 1)
+    q = np.array([g[h]["q"] for h in heads], dtype=np.float64).reshape(len(heads), 2, 1)
+    return g, q, k
+
+
+@pytest.mark.parametrize("head", ["head0", "head1"])
+def test_worked_example_single_head(head):
+    g, q, k = _example_inputs([head])
+    a = co.window_attention(q, k, scale=1.0)
+    # causal mask inside the window: row 0 (position 2) must not see key 3
+    assert a[0, 0, 3] == 0.0 and a[0, 1, 3] > 0.0
+    a_obs = co.observed(a, 2)
+    want = np.array([[_f(x) for x in row] for row in g[head]["a_obs"]])
+    np.testing.assert_allclose(a_obs[0], want, rtol=1e-14)
+    np.testing.assert_allclose(co.column_variance(a_obs, 1)[0], [_f(x) for x in g[head]["var_unbiased"]], rtol=1e-13)
+    np.testing.assert_allclose(co.column_variance(a_obs, 0)[0], [_f(x) / 2 for x in g[head]["var_unbiased"]], rtol=1e-13)
+    np.testing.assert_allclose(co.head_indicator(a_obs, 200.0, 1)[0], [_f(x) for x in g[head]["indicator_gamma200"]], rtol=1e-13)
+    np.testing.assert_allclose(co.shift(a_obs, 1)[0], _f(g[head]["V"]), rtol=1e-13)
+    h_want = sum(_f(c) * math.log(_f(arg)) for c, arg in g[head]["H_terms"])
+    np.testing.assert_allclose(co.dispersion(a_obs)[0], h_want, rtol=1e-13)
+
+
+def test_worked_example_gqa_pool_and_preference():
+    g, q, k = _example_inputs(["head0", "head1"])          # two query heads on one KV head
+    p = co.OracleParams(scale=1.0, gamma=200.0, tau1=1.0, tau2=1.0, var_correction=1, pool_kernel=1)
+    out = co.layer_pass(q, k, p)
+    i0 = [Fraction(x) for x in g["head0"]["indicator_gamma200"]]
+    i1 = [Fraction(x) for x in g["head1"]["indicator_gamma200"]]
+    want = [float((a + b) / 2) for a, b in zip(i0, i1)]
+    np.testing.assert_allclose(out["indicator"][0], want, rtol=1e-13)
+    h = [sum(_f(c) * math.log(_f(arg)) for c, arg in g[hd]["H_terms"]) for hd in ("head0", "head1")]
+    v = [_f(g[hd]["V"]) for hd in ("head0", "head1")]
+    np.testing.assert_allclose(out["H"], (h[0] + h[1]) / 2, rtol=1e-13)
+    np.testing.assert_allclose(out["V"], (v[0] + v[1]) / 2, rtol=1e-13)
+    np.testing.assert_allclose(out["pref"], (h[0] + h[1]) / 2 * (v[0] + v[1]) / 2, rtol=1e-13)
+    # tau exponents of Eq. (6)
+    p2 = co.OracleParams(scale=1.0, tau1=0.5, tau2=2.0, pool_kernel=1)
+    out2 = co.layer_pass(q, k, p2)
+    np.testing.assert_allclose(out2["pref"], ((h[0] + h[1]) / 2) ** 2 * math.sqrt((v[0] + v[1]) / 2), rtol=1e-13)
+    # pooling with width 3 over two columns: both become the larger one
+    p3 = co.OracleParams(scale=1.0, pool_kernel=3)
+    np.testing.assert_allclose(co.layer_pass(q, k, p3)["indicator"][0], [max(want)] * 2, rtol=1e-13)
+
+
+# ---------------------------------------------------------------- softmax
+def test_softmax_rows_sum_to_one_and_match_scipy():
+    rng = np.random.default_rng(0)
+    q = rng.standard_normal((4, 8, 16))
+    k = rng.standard_normal((2, 50, 16))
+    s = co.window_logits(q, k)
+    a = co.softmax_rows(s)
+    np.testing.assert_allclose(a.sum(-1), 1.0, atol=1e-12)
+    np.testing.assert_allclose(a, scipy.special.softmax(s, axis=-1), rtol=1e-12, atol=0)
+    # causal triangle over the last S_w keys: row r sees keys up to N_p + r
+    n_p = 50 - 8
+    for r in range(8):
+        assert np.all(a[:, r, n_p + r + 1:] == 0.0)
+        assert np.all(a[:, r, : n_p + r + 1] > 0.0)
+    # logits: head h reads KV head h // G, scaled by 1/sqrt(d)
+    want = np.einsum("c,c->", q[3, 2], k[1, 7]) / 4.0
+    np.testing.assert_allclose(s[3, 2, 7], want, rtol=1e-13)
+    # agrees with torch's softmax on the masked logits
+    ta = torch.softmax(torch.from_numpy(s), dim=-1).numpy()
+    np.testing.assert_allclose(a, ta, rtol=1e-12)
+
+
+# ---------------------------------------------------------------- closed forms: uniform attention
+def test_zero_queries_closed_forms():
+    h_q, h_kv, s_w, n, d = 2, 1, 6, 40, 8
+    n_p = n - s_w
+    q = np.zeros((h_q, s_w, d))
+    k = np.random.default_rng(1).standard_normal((h_kv, n, d))
+    a_obs = co.observed(co.window_attention(q, k), s_w)
+    n_r = [n_p + r + 1 for r in range(s_w)]
+    h_want = sum(n_p * math.log(x) / x for x in n_r)
+    np.testing.assert_allclose(co.dispersion(a_obs), [h_want] * h_q, rtol=1e-12)
+    var_want = statistics.variance([1.0 / x for x in n_r])          # unbiased
+    pvar_want = statistics.pvariance([1.0 / x for x in n_r])        # biased
+    np.testing.assert_allclose(co.shift(a_obs, 1), [n_p * var_want] * h_q, rtol=1e-10)
+    np.testing.assert_allclose(co.shift(a_obs, 0), [n_p * pvar_want] * h_q, rtol=1e-10)
+    mean_want = statistics.fmean([1.0 / x for x in n_r])
+    np.testing.assert_allclose(co.head_indicator(a_obs, 200.0, 1), mean_want + 200.0 * var_want, rtol=1e-10)
+
+
+def test_variance_matches_numpy():
+    a = np.random.default_rng(2).random((3, 9, 31))
+    np.testing.assert_allclose(co.column_variance(a, 1), np.var(a, axis=-2, ddof=1), rtol=1e-12)
+    np.testing.assert_allclose(co.column_variance(a, 0), np.var(a, axis=-2, ddof=0), rtol=1e-12)
+
+
+def test_entropy_terms_nonnegative_and_zero_log_zero():
+    a = np.array([[[0.0, 0.25, 0.5], [1.0, 0.0, 0.0]]])
+    h = co.dispersion(a)
+    want = -(0.25 * math.log(0.25) + 0.5 * math.log(0.5))
+    np.testing.assert_allclose(h, [want], rtol=1e-14)
+
+
+# ---------------------------------------------------------------- static attention: no temporal shift
+def test_static_attention_has_zero_shift():
+    row = np.random.default_rng(3).random(57)
+    row /= row.sum() * 1.3
+    a_obs = np.broadcast_to(row, (2, 16, 57)).copy()
+    # zero up to the rounding of the row sum (a few ulp of the mean, squared)
+    assert np.all(co.shift(a_obs, 1) <= 1e-28 * np.sum(row ** 2))
+    np.testing.assert_allclose(co.head_indicator(a_obs, 200.0, 1), a_obs[:, 0, :], rtol=1e-14)
+
+
+def test_static_attention_from_q_and_k():
+    # identical window queries, window keys pushed out of sight => identical rows
+    rng = np.random.default_rng(4)
+    s_w, n, d = 8, 200, 16
+    q = np.repeat(rng.standard_normal((2, 1, d)), s_w, axis=1)
+    k = rng.standard_normal((1, n, d))
+    k[:, n - s_w:, :] = 0.0
+    k[:, n - s_w:, 0] = -1e4 * np.sign(q[0, 0, 0])
+    q[1] = q[0]
+    a_obs = co.observed(co.window_attention(q, k), s_w)
+    mu = a_obs.mean(axis=-2)
+    assert np.all(co.shift(a_obs, 1) <= 1e-12 * np.sum(mu ** 2, axis=-1))
+
+
+# ---------------------------------------------------------------- indicator
+def test_indicator_reduces_to_window_mean_and_is_linear_in_gamma():
+    a_obs = np.random.default_rng(5).random((2, 12, 33)) / 40.0
+    p0 = co.OracleParams(gamma=0.0, pool_kernel=1)
+    np.testing.assert_allclose(co.eviction_indicator(a_obs, 1, p0), a_obs.mean(axis=-2), rtol=1e-13)
+    i200 = co.head_indicator(a_obs, 200.0, 1)
+    i0 = co.head_indicator(a_obs, 0.0, 1)
+    np.testing.assert_allclose(i200 - i0, 200.0 * np.var(a_obs, axis=-2, ddof=1), rtol=1e-10)
+
+
+def test_gqa_duplicate_heads_and_identity():
+    a_one = np.random.default_rng(6).random((1, 8, 21)) / 30.0
+    a_dup = np.repeat(a_one, 4, axis=0)
+    p = co.OracleParams(pool_kernel=1)
+    np.testing.assert_allclose(co.eviction_indicator(a_dup, 4, p), co.eviction_indicator(a_one, 1, p), rtol=1e-13)
+    i_q = np.arange(12, dtype=np.float64).reshape(4, 3)
+    np.testing.assert_array_equal(co.group_reduce(i_q, 1), i_q)
+    np.testing.assert_allclose(co.group_reduce(i_q, 2), [[1.5, 2.5, 3.5], [7.5, 8.5, 9.5]])
+
+
+@pytest.mark.parametrize("w", [1, 3, 7, 9])
+def test_max_pool_matches_torch(w):
+    x = np.random.default_rng(7).random((3, 50))
+    want = torch.nn.functional.max_pool1d(torch.from_numpy(x).unsqueeze(0), w, stride=1, padding=w // 2)[0].numpy()
+    got = co.max_pool(x, w)
+    np.testing.assert_array_equal(got, want)
+    assert np.all(got >= x)
+    if w == 1:
+        np.testing.assert_array_equal(got, x)
+
+
+# ---------------------------------------------------------------- allocation (Eq. 7 / Eq. 9, Prop. 1)
+def _brute_force_alloc(pref, total, window, n):
+    """Materialise every priority P_l/(s + 1/2) for seat counts s = window..n-1, take the top R."""
+    m1 = len(pref)
+    if m1 * n <= total:
+        return [n] * m1
+    if all(p == 0.0 for p in pref):
+        pref = [1.0] * m1
+    seats = [(-(pref[l] / (s + 0.5)), l, s) for l in range(m1) for s in range(window, n)]
+    seats.sort()
+    r = total - m1 * window
+    out = [window] * m1
+    for _, l, _s in seats[:r]:
+        out[l] += 1
+    return out
+
+
+def test_allocation_brute_force_tiny():
+    rng = np.random.default_rng(8)
+    for _ in range(400):
+        m1 = int(rng.integers(1, 5))
+        window = int(rng.integers(1, 4))
+        n = int(rng.integers(window + 1, 24))
+        total = int(rng.integers(m1 * window, 65))
+        pref = [float(x) for x in rng.choice([0.0, 0.5, 1.0, 2.0, 3.0, 7.5], size=m1)]
+        got = co.cascade_allocate(pref, total, window, n)
+        assert got == _brute_force_alloc(pref, total, window, n), (pref, total, window, n)
+
+
+def test_allocation_invariants():
+    rng = np.random.default_rng(9)
+    for _ in range(200):
+        m1 = int(rng.integers(1, 33))
+        window, n = 32, int(rng.integers(200, 5000))
+        total = int(rng.integers(m1 * window, m1 * n + 50))
+        pref = rng.random(m1) * rng.choice([1.0, 10.0, 1e-3], size=m1)
+        b = co.cascade_allocate(pref, total, window, n)
+        assert sum(b) == min(total, m1 * n)
+        assert all(window <= x <= n for x in b)
+        for i, j in itertools.combinations(range(m1), 2):
+            if pref[i] >= pref[j]:
+                assert b[i] >= b[j]
+            if pref[i] <= pref[j]:
+                assert b[i] <= b[j]
+
+
+def test_allocation_tracks_eq7_when_unclamped():
+    rng = np.random.default_rng(10)
+    for _ in range(50):
+        m1 = 8
+        pref = 1.0 + rng.random(m1)                  # ratios <= 2: neither floor nor cap binds
+        total, window, n = 8 * 1024, 32, 100000
+        b = co.cascade_allocate(pref, total, window, n)
+        exact = pref / pref.sum() * total
+        assert np.max(np.abs(np.array(b) - exact)) <= 1.0
+
+
+def test_allocation_equal_preferences_split_evenly():
+    assert co.cascade_allocate([2.0] * 4, 4 * 300, 32, 5000) == [300] * 4
+    b = co.cascade_allocate([2.0] * 4, 4 * 300 + 2, 32, 5000)
+    assert sorted(b) == [300, 300, 301, 301] and b[:2] == [301, 301]       # ties to the lower layer
+    assert co.cascade_allocate([0.0] * 3, 3 * 100, 32, 5000) == [100] * 3    # all-zero => uniform
+    assert co.cascade_allocate([0.0, 1.0], 500, 32, 5000) == [32, 468]        # a zero layer keeps its window
+    assert co.cascade_allocate([1.0, 3.0], 10_000, 32, 100) == [100, 100]     # everything fits
+    with pytest.raises(ValueError):
+        co.cascade_allocate([1.0, 1.0], 63, 32, 100)
+    with pytest.raises(ValueError):
+        co.cascade_allocate([1.0, float("nan")], 640, 32, 100)
+    with pytest.raises(ValueError):
+        co.cascade_allocate([1.0, -1.0], 640, 32, 100)
+
+
+def test_allocation_stage_monotone_prop1():
+    rng = np.random.default_rng(11)
+    for _ in range(300):
+        n_layers = int(rng.integers(2, 9))
+        window = int(rng.integers(1, 5))
+        n = int(rng.integers(10, 60))
+        total = int(rng.integers(n_layers * window, n_layers * n))
+        pref = rng.choice([0.25, 0.5, 1.0, 1.0, 2.0, 3.0, 0.0], size=n_layers).astype(float)
+        prev = None
+        for m in range(n_layers):
+            cur = co.cascade_allocate(pref[: m + 1], total, window, n)
+            if prev is not None:
+                assert all(c <= p for c, p in zip(cur, prev)), (pref, total, window, n, m)
+            prev = cur
+
+
+# ---------------------------------------------------------------- top-k and compaction (Eq. 12)
+def test_topk_brute_force_and_ties():
+    rng = np.random.default_rng(12)
+    for _ in range(200):
+        n = int(rng.integers(1, 40))
+        x = rng.choice([0.0, 0.1, 0.2, 0.3, 0.5], size=n)        # many ties
+        k = int(rng.integers(0, n + 1))
+        pairs = sorted(((-x[i], i) for i in range(n)))
+        want = sorted(i for _, i in pairs[:k])
+        got = co.select_topk(x, k)
+        assert list(got) == want
+    x = np.array([1.0, 3.0, 3.0, 2.0, 3.0])
+    assert list(co.select_topk(x, 2)) == [1, 2]                   # lowest positions among equals
+    assert list(co.select_topk(x, 4)) == [1, 2, 3, 4]
+
+
+def test_topk_matches_torch_as_a_set_when_distinct():
+    x = np.random.default_rng(13).permutation(500).astype(np.float64)
+    got = co.select_topk(x, 37)
+    want = torch.topk(torch.from_numpy(x), 37).indices.numpy()
+    assert set(got.tolist()) == set(want.tolist())
+    assert np.all(np.diff(got) > 0)
+
+
+def test_compaction_keeps_selected_rows_then_window():
+    rows = np.arange(10 * 3, dtype=np.float64).reshape(10, 3)
+    idx = np.array([1, 4, 6])
+    out = co.compact(rows, idx, 2)
+    np.testing.assert_array_equal(out[:3], rows[idx])
+    np.testing.assert_array_equal(out[3:], rows[8:])
+    k_hat, v_hat, i_hat, got_idx = co.evict(rows, rows + 100, np.array([5., 1., 7., 7., 0., 2., 9., 3.]), 2 + 3, 2)
+    assert list(got_idx) == [2, 3, 6]
+    np.testing.assert_array_equal(k_hat, np.concatenate([rows[[2, 3, 6]], rows[8:]]))
+    np.testing.assert_array_equal(v_hat, k_hat + 100)
+    np.testing.assert_array_equal(i_hat, [7., 7., 9.])
+
+
+# ---------------------------------------------------------------- whole pass on the Tiny config
+@pytest.fixture(scope="module")
+def tiny():
+    cfg = CONFIGS[1]
+    p = co.OracleParams()
+    layers = [make_layer(cfg, l, 0) for l in range(cfg.n_layers)]
+    outs = [co.layer_pass(x["q_win"].double().numpy(), x["k"].double().numpy(), p) for x in layers]
+    return cfg, layers, outs
+
+
+def test_tiny_preferences_differ_and_heavy_hitters_survive(tiny):
+    cfg, layers, outs = tiny
+    assert outs[1]["H"] < outs[0]["H"]            # 4x temperature => more peaked rows => lower entropy
+    assert outs[0]["pref"] > 0 and outs[1]["pref"] > 0 and outs[0]["pref"] != outs[1]["pref"]
+    budgets = co.cascade_allocate([o["pref"] for o in outs], cfg.total_budget, cfg.window, cfg.seq_len)
+    assert sum(budgets) == cfg.total_budget and budgets[1] > budgets[0]
+    # each planted key (+3 logits for every window query) dominates its pooling neighbourhood:
+    # 8 planted keys x 7 pooled positions fit in the top 64
+    heavy = layers[0]["meta"]["heavy"][0].numpy()
+    for g in range(cfg.n_kv_heads):
+        kept = set(co.select_topk(outs[0]["indicator"][g], 64).tolist())
+        assert set(heavy.tolist()) <= kept
+
+
+def test_tiny_cascade_equals_one_shot_thm2(tiny):
+    cfg, layers, outs = tiny
+    prefs = [o["pref"] for o in outs]
+    inds = [o["indicator"] for o in outs]
+    ks = [x["k"].double().numpy() for x in layers]
+    vs = [x["v"].double().numpy() for x in layers]
+    budgets, shot = co.one_shot(prefs, inds, ks, vs, cfg.total_budget, cfg.window)
+    history, cache = co.cascade_manage(prefs, inds, ks, vs, cfg.total_budget, cfg.window)
+    assert history[-1] == budgets
+    assert history[0] == [min(cfg.total_budget, cfg.seq_len)]
+    for l in range(cfg.n_layers):
+        for g in range(cfg.n_kv_heads):
+            np.testing.assert_array_equal(cache[l]["pos"][g], shot[l]["pos"][g])
+            np.testing.assert_array_equal(cache[l]["k"][g], shot[l]["k"][g])
+            np.testing.assert_array_equal(cache[l]["v"][g], shot[l]["v"][g])
+            np.testing.assert_array_equal(cache[l]["ind"][g], shot[l]["ind"][g])
+            assert shot[l]["k"][g].shape == (budgets[l], cfg.head_dim)
+            np.testing.assert_array_equal(shot[l]["k"][g][-cfg.window:], ks[l][g][-cfg.window:])
+
+
+def test_cascade_equals_one_shot_many_layers_with_ties():
+    # pooled indicators tie heavily at the cut; Thm. 2 must still hold with the (value, position) order
+    rng = np.random.default_rng(14)
+    n_layers, h_kv, n, window, d = 5, 2, 90, 6, 4
+    prefs = list(rng.random(n_layers) + 0.1)
+    inds = [co.max_pool(rng.choice([0.1, 0.2, 0.3, 0.4], size=(h_kv, n - window)), 5) for _ in range(n_layers)]
+    ks = [rng.standard_normal((h_kv, n, d)) for _ in range(n_layers)]
+    vs = [rng.standard_normal((h_kv, n, d)) for _ in range(n_layers)]
+    budgets, shot = co.one_shot(prefs, inds, ks, vs, 150, window)
+    history, cache = co.cascade_manage(prefs, inds, ks, vs, 150, window)
+    assert history[-1] == budgets and sum(budgets) == 150
+    for l in range(n_layers):
+        for g in range(h_kv):
+            np.testing.assert_array_equal(cache[l]["pos"][g], shot[l]["pos"][g])
+            np.testing.assert_array_equal(cache[l]["k"][g], shot[l]["k"][g])
