@@ -1,0 +1,186 @@
+/*
+ * libcake — prefill-time KV-cache eviction pass of CAKE (cascading and adaptive KV-cache
+ * eviction with layer preferences) for one AMD MI355X (gfx950).
+ *
+ * C ABI.  No C++ or framework types cross this boundary: plain pointers, sizes and PODs.
+ *
+ * Notation (the paper's, with N for its sequence length S):
+ *   B batch, L layers, H_q query heads, H_kv KV heads, G = H_q / H_kv, d head_dim,
+ *   N rows of K/V per head (prompt length, observation window included), S_w window,
+ *   N_p = N - S_w prefix length (the positions that are scored and may be evicted),
+ *   B_total cache budget per KV head summed over layers, B_l budget of layer l
+ *   (window tokens included), k_l = B_l - S_w prefix tokens retained.
+ *
+ * Conventions for every call
+ *   - Returns CAKE_OK (0) or a negative cake_status; cake_last_error() gives the reason
+ *     (thread-local string, valid until the thread's next failing call).
+ *   - "device" pointers are HIP device memory owned by the caller; "host" pointers are
+ *     ordinary process memory owned by the caller.  The library never allocates or frees
+ *     device memory and keeps no state between calls.
+ *   - Device work is enqueued on `stream` (a hipStream_t passed as void*; NULL = default
+ *     stream) and the call returns without synchronising.  Host arrays are consumed before
+ *     the call returns.  cake_cascade_allocate is host-only and synchronous.
+ *   - Inputs are never written.  Outputs must not overlap inputs or each other.
+ *   - A "table" is a DEVICE array of n_layers device pointers, one base pointer per layer,
+ *     so that a whole multi-layer pass is a handful of launches.
+ *   - Ragged per-layer arrays: where sequences of a batch keep different numbers of rows,
+ *     a per-layer array [B, H_kv, rows, ...] is laid out with row capacity
+ *     cap_l = max over b of the per-sequence row count; rows past a sequence's own count
+ *     are neither read nor written.
+ *   - Invalid arguments are rejected on the host before anything is launched.
+ */
+#ifndef CAKE_H_
+#define CAKE_H_
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+  CAKE_OK = 0,
+  CAKE_ERR_INVALID_ARG = -1,  /* null pointer, non-positive size, N <= S_w, k > cur_len, ... */
+  CAKE_ERR_UNSUPPORTED = -2,  /* dtype / head_dim / window / group size with no kernel */
+  CAKE_ERR_WORKSPACE = -3,    /* workspace missing, misaligned (256 B) or too small */
+  CAKE_ERR_HIP = -4           /* a HIP runtime call or launch failed */
+} cake_status;
+
+typedef enum { CAKE_BF16 = 0, CAKE_F32 = 1 } cake_dtype;
+
+/* Problem shape.  Supported: head_dim 64 or 128, window 32 or 64, 1 <= G <= 8,
+ * n_layers <= 1024, n_layers * batch unbounded (large passes are split into launches). */
+typedef struct {
+  int32_t batch;       /* B */
+  int32_t n_layers;    /* layers handled by this call (1 for strict per-layer cascading) */
+  int32_t n_q_heads;   /* H_q */
+  int32_t n_kv_heads;  /* H_kv, divides H_q */
+  int32_t head_dim;    /* d */
+  int32_t seq_len;     /* N, only read by cake_window_scores / cake_workspace_bytes */
+  int32_t window;      /* S_w */
+  int32_t dtype;       /* cake_dtype of Q, K, V */
+} cake_shape;
+
+/* Method parameters (Sec. 4.1 Eq. 6, Sec. 4.3 Eq. 11 and the implementation appendix). */
+typedef struct {
+  float scale;             /* softmax scale; 0 selects 1/sqrt(head_dim) (Sec. 2) */
+  float gamma;             /* weight of Var in the indicator, the paper fixes 200 */
+  float tau1;              /* temperature of the dispersion H in Eq. 6 */
+  float tau2;              /* temperature of the shift V in Eq. 6 */
+  int32_t var_correction;  /* 1: unbiased Var over the S_w rows (divide by S_w-1); 0: biased */
+  int32_t pool_kernel;     /* odd width of the stride-1 max-pool over prefix positions; 1 = off */
+} cake_params;
+
+/* Library version (major*10000 + minor*100 + patch). */
+int cake_version(void);
+
+/* Reason for the calling thread's most recent failure; "" if none. */
+const char* cake_last_error(void);
+
+/* Bytes of device workspace that cake_window_scores, cake_layer_preference and
+ * cake_select_topk need for `shape` (the maximum over the three).  The workspace must be
+ * 256-byte aligned.  cake_layer_preference reads what cake_window_scores left in it, so the
+ * same buffer must be passed to both with nothing else written in between. */
+int cake_workspace_bytes(const cake_shape* shape, size_t* bytes /* host, out */);
+
+/*
+ * Observation-window scores (Sec. 2 attention weights; Sec. 4.1 recent-window submatrix
+ * A[-S_w:, :-S_w]; Sec. 3 Eq. 4-5; Sec. 4.3 Eq. 11).
+ *
+ * For every layer, sequence and query head h (KV head h / G) the last S_w queries attend to
+ * all N keys: logits scale*<q_r, k_j>, key j hidden from window row r when j > N_p + r,
+ * softmax over the visible keys.  On the prefix columns j < N_p of those rows it forms
+ *   per (h, j): Mean and Var over the S_w rows, I_q = Mean + gamma*Var          (Eq. 11)
+ *   per KV head: I = mean of I_q over the G heads of the group, then max-pooled
+ *   per h: H_h = -sum p ln p (Eq. 4), V_h = sum_j Var (Eq. 5)  -> partial sums in workspace
+ *
+ *   q_win      table; q_win[l] -> [B, H_q, S_w, d] window queries, strides q_strides
+ *   k          table; k[l]     -> [B, H_kv, N, d] keys (window rows are the last S_w)
+ *   q_strides  host [3]: element strides of batch, head, token; d is contiguous
+ *   k_strides  host [3]: likewise for k
+ *   indicator  table; indicator[l] -> [B, H_kv, N_p] f32, contiguous, written
+ *   workspace  device scratch of at least cake_workspace_bytes(shape)
+ */
+int cake_window_scores(const cake_shape* shape, const cake_params* params,
+                       const void* const* q_win, const void* const* k,
+                       const int64_t* q_strides, const int64_t* k_strides,
+                       float* const* indicator,
+                       void* workspace, size_t workspace_bytes, void* stream);
+
+/*
+ * Layer preference (Sec. 4.1 Eq. 6): H_l and V_l are the means over the layer's query heads
+ * of H_h and V_h, reduced in a fixed order from the partial sums cake_window_scores left in
+ * `workspace`; P_l = H_l^(1/tau1) * V_l^(1/tau2).
+ *
+ *   pref  device [B, n_layers] f64, written
+ *   hv    device [B, n_layers, 2] f64 = (H_l, V_l), written; may be NULL
+ */
+int cake_layer_preference(const cake_shape* shape, const cake_params* params,
+                          const void* workspace, size_t workspace_bytes,
+                          double* pref, double* hv, void* stream);
+
+/*
+ * Preference-prioritised allocation in its cascading form (Sec. 4.1 Eq. 7; Sec. 4.2 Eq. 9,
+ * Prop. 1; Alg. 1 budget step).  HOST function, no GPU involved.
+ *
+ * Stage m = n_seen - 1: integer budgets B_l^(m), l = 0..m, proportional to pref[l] over the
+ * layers seen so far.  Integers come from divisor (Webster) apportionment: each layer first
+ * holds its S_w window tokens, the rest are awarded one by one to the layer with the largest
+ * pref[l] / (B_l + 1/2) among layers below N, ties to the lower layer.  Hence
+ *   sum_l B_l = min(total_budget, n_seen*N),  S_w <= B_l <= N,
+ *   pref[a] >= pref[b] => B_a >= B_b,  and B_l^(m+1) <= B_l^(m) (Prop. 1, non-strict).
+ * If every layer fits whole (n_seen*N <= total_budget) every B_l = N: nothing to evict.
+ * All-zero preferences are treated as equal.  n_seen = L gives Eq. 7.
+ *
+ *   pref     host [n_seen], finite and >= 0
+ *   budgets  host [n_seen], written
+ * Errors: NaN/negative preference, total_budget < n_seen*S_w, N <= S_w.
+ */
+int cake_cascade_allocate(const double* pref, int32_t n_seen, int64_t total_budget,
+                          int32_t window, int32_t seq_len, int32_t* budgets);
+
+/*
+ * Per-head top-k of the indicator (Sec. 4.3 Eq. 12, D_l = TopK(I_l, B_l); the window
+ * positions carry Omega in Eq. 11 and are kept structurally, so k counts prefix tokens).
+ *
+ * For each layer l, sequence b and KV head: the k[l*B+b] entries of the first
+ * cur_len[l*B+b] indicator values that are largest under (value descending, position
+ * ascending); positions are written in ascending order.  Values are compared as IEEE floats
+ * (-0 = +0); NaNs are not supported.
+ *
+ *   indicator  table; indicator[l] -> [B, H_kv, max_b cur_len] f32
+ *   cur_len    host [n_layers*B]: current evictable length (N_p at first, a previous k later)
+ *   k          host [n_layers*B]: 0 <= k <= cur_len
+ *   idx        table; idx[l] -> [B, H_kv, max_b k] int32, written
+ */
+int cake_select_topk(const cake_shape* shape, const float* const* indicator,
+                     const int32_t* cur_len, const int32_t* k, int32_t* const* idx,
+                     void* workspace, size_t workspace_bytes, void* stream);
+
+/*
+ * EVICT's compaction (Sec. 4.3 Eq. 12, K_hat = K[D,:], V_hat = V[D,:]; Alg. 1 cache and
+ * indicator update).  Gathers the selected prefix rows and appends the S_w window rows.
+ *
+ * Sequence b of layer l holds cur_len prefix rows followed by its S_w window rows
+ * (rows cur_len .. cur_len+S_w-1).  Output: k[l*B+b] gathered rows, then the window rows.
+ *
+ *   k_in, v_in   tables; [B, H_kv, rows, d] with per-layer element strides kv_strides
+ *   kv_strides   host [n_layers][3]: batch, head, token strides of k_in[l] and v_in[l]
+ *   cur_len, k   host [n_layers*B] as in cake_select_topk
+ *   idx          table; idx[l] -> [B, H_kv, max_b k] int32 ascending positions < cur_len
+ *   ind_in       table of [B, H_kv, max_b cur_len] f32, or NULL to skip the indicator
+ *   k_out, v_out tables; [B, H_kv, max_b k + S_w, d] contiguous, written
+ *   ind_out      table of [B, H_kv, max_b k] f32, written; NULL iff ind_in is NULL
+ */
+int cake_compact_kv(const cake_shape* shape,
+                    const void* const* k_in, const void* const* v_in, const int64_t* kv_strides,
+                    const int32_t* cur_len, const int32_t* k, const int32_t* const* idx,
+                    const float* const* ind_in,
+                    void* const* k_out, void* const* v_out, float* const* ind_out,
+                    void* stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* CAKE_H_ */

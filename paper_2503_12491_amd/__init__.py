@@ -1,0 +1,10 @@
+"""MI355X-native prefill eviction pass of CAKE behind a C ABI (libcake.so).
+
+The functions below are thin ctypes wrappers with the names of include/cake.h; all
+arithmetic runs in the HIP kernels.  There is no CPU or PyTorch fallback: calling
+anything without a built libcake.so raises.
+"""
+from .binding import (CAKE_BF16, CAKE_F32, CakeError, cake_cascade_allocate, cake_compact_kv,  # noqa: F401
+                      cake_layer_preference, cake_select_topk, cake_version, cake_window_scores,
+                      cake_workspace_bytes, make_params, make_shape, ptr_table)
+from .driver import EvictionPass, PassResult  # noqa: F401

@@ -1,0 +1,106 @@
+"""Python names for the C ABI of libcake (include/cake.h).  Argument marshalling only."""
+from __future__ import annotations
+
+import ctypes
+from typing import Optional, Sequence
+
+import torch
+
+from ._ffi import cake_params, cake_shape, load
+
+CAKE_BF16, CAKE_F32 = 0, 1
+
+
+class CakeError(RuntimeError):
+    def __init__(self, code: int, message: str):
+        super().__init__(f"libcake error {code}: {message}")
+        self.code = code
+
+
+def _check(rc: int) -> None:
+    if rc != 0:
+        raise CakeError(rc, load().cake_last_error().decode())
+
+
+def make_shape(batch, n_layers, n_q_heads, n_kv_heads, head_dim, seq_len, window, dtype) -> cake_shape:
+    if isinstance(dtype, torch.dtype):
+        dtype = {torch.bfloat16: CAKE_BF16, torch.float32: CAKE_F32}[dtype]
+    return cake_shape(batch, n_layers, n_q_heads, n_kv_heads, head_dim, seq_len, window, dtype)
+
+
+def make_params(scale=0.0, gamma=200.0, tau1=1.0, tau2=1.0, var_correction=1, pool_kernel=7) -> cake_params:
+    return cake_params(scale, gamma, tau1, tau2, var_correction, pool_kernel)
+
+
+def ptr_table(tensors: Sequence[torch.Tensor]) -> torch.Tensor:
+    """Device array of the tensors' base addresses (one per layer)."""
+    dev = tensors[0].device
+    return torch.tensor([t.data_ptr() for t in tensors], dtype=torch.int64).to(dev)
+
+
+def _ptr(x) -> Optional[int]:
+    if x is None:
+        return None
+    if isinstance(x, torch.Tensor):
+        return x.data_ptr()
+    return int(x)
+
+
+def _stream(stream) -> Optional[int]:
+    if stream is None:
+        return torch.cuda.current_stream().cuda_stream or None
+    if isinstance(stream, torch.cuda.Stream):
+        return stream.cuda_stream or None
+    return int(stream) or None
+
+
+def _i64(vals):
+    return (ctypes.c_int64 * len(vals))(*[int(v) for v in vals])
+
+
+def _i32(vals):
+    return (ctypes.c_int32 * len(vals))(*[int(v) for v in vals])
+
+
+def cake_version() -> int:
+    return load().cake_version()
+
+
+def cake_workspace_bytes(shape: cake_shape) -> int:
+    out = ctypes.c_size_t(0)
+    _check(load().cake_workspace_bytes(ctypes.byref(shape), ctypes.byref(out)))
+    return out.value
+
+
+def cake_window_scores(shape, params, q_win, k, q_strides, k_strides, indicator, workspace, stream=None) -> None:
+    _check(load().cake_window_scores(ctypes.byref(shape), ctypes.byref(params), _ptr(q_win), _ptr(k),
+                                     _i64(q_strides), _i64(k_strides), _ptr(indicator), _ptr(workspace),
+                                     workspace.numel() * workspace.element_size(), _stream(stream)))
+
+
+def cake_layer_preference(shape, params, workspace, pref, hv=None, stream=None) -> None:
+    _check(load().cake_layer_preference(ctypes.byref(shape), ctypes.byref(params), _ptr(workspace),
+                                        workspace.numel() * workspace.element_size(), _ptr(pref), _ptr(hv),
+                                        _stream(stream)))
+
+
+def cake_cascade_allocate(pref: Sequence[float], total_budget: int, window: int, seq_len: int) -> list:
+    n = len(pref)
+    p = (ctypes.c_double * n)(*[float(x) for x in pref])
+    out = (ctypes.c_int32 * n)()
+    _check(load().cake_cascade_allocate(p, n, int(total_budget), int(window), int(seq_len), out))
+    return list(out)
+
+
+def cake_select_topk(shape, indicator, cur_len, k, idx, workspace=None, stream=None) -> None:
+    ws_bytes = 0 if workspace is None else workspace.numel() * workspace.element_size()
+    _check(load().cake_select_topk(ctypes.byref(shape), _ptr(indicator), _i32(cur_len), _i32(k), _ptr(idx),
+                                   _ptr(workspace), ws_bytes, _stream(stream)))
+
+
+def cake_compact_kv(shape, k_in, v_in, kv_strides, cur_len, k, idx, ind_in, k_out, v_out, ind_out,
+                    stream=None) -> None:
+    flat = [s for layer in kv_strides for s in layer]
+    _check(load().cake_compact_kv(ctypes.byref(shape), _ptr(k_in), _ptr(v_in), _i64(flat), _i32(cur_len), _i32(k),
+                                  _ptr(idx), _ptr(ind_in), _ptr(k_out), _ptr(v_out), _ptr(ind_out),
+                                  _stream(stream)))

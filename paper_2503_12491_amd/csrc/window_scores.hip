@@ -1,0 +1,470 @@
+// cake_window_scores / cake_layer_preference: observation-window attention statistics.
+//
+// Sec. 2 (attention weights), Sec. 4.1 (recent-window submatrix A[-S_w:, :-S_w]),
+// Sec. 3 Eq. 4-5 (dispersion, shift), Sec. 4.3 Eq. 11 (Mean + gamma*Var indicator).
+//
+// A "slice" is one (layer, sequence, KV head).  Its G*S_w window rows (G query heads of the
+// group, S_w rows each) attend to the slice's N keys.  The softmax normaliser of a row needs
+// every key, the column statistics need the normalised weights, so the keys are visited twice:
+//
+//   pass 1  logits via MFMA (keys on the M side, window rows on the N side, so that each lane
+//           owns ONE window row per 32-row block and keeps a running (reference, sum) pair for
+//           it with no cross-lane traffic); partial pairs per chunk of keys        -> workspace
+//   combine partial pairs -> log2-domain normaliser per window row                  -> workspace
+//   pass 2  logits again (window rows on the M side, keys on the N side, so that each lane owns
+//           ONE key column and the Mean/Var over the S_w rows are in-register sums); weights
+//           p = exp2(t), t = logit*scale*log2(e) - lse2; per column sum p, sum p^2; entropy
+//           sum p*t; group mean of I_q through LDS                      -> un-pooled indicator
+//   pool    stride-1 max-pool over prefix positions                              -> indicator
+//   pref    fixed-order fp64 reduction of the per-chunk entropy/variance sums    -> P_l, H_l, V_l
+//
+// One workgroup = G wavefronts = one chunk of keys of one slice; wave w serves query head
+// g*G + w.  K tiles of 64 keys are staged through LDS once per workgroup and shared by the G
+// waves.  Everything is deterministic: no float atomics, fixed reduction orders.
+#include <cmath>
+
+#include "cake_internal.h"
+
+namespace cake {
+namespace {
+
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef float f32x16 __attribute__((ext_vector_type(16)));
+
+constexpr int kTileKeys = 64;        // keys staged per LDS tile (two 32-key MFMA sub-tiles)
+constexpr float kMasked = -1.0e30f;  // stands for -inf without producing NaN in differences
+constexpr float kRescale = 40.0f;    // pass 1 re-references a row when a logit exceeds it by 2^40
+
+// MFMA operand fragments.  For both the A and the B operand of the 32x32 instructions lane
+// (c32, hh) supplies, for its row/column c32, a group of consecutive reduction elements chosen
+// by hh; A and B use the same element order, so the dot products come out complete.
+template <typename T> struct Frag;
+template <> struct Frag<__bf16> {
+  using type = bf16x8;
+  static constexpr int kElems = 16;  // reduction elements per MFMA
+  static __device__ __forceinline__ type load(const void* row, int step, int hh) {
+    return *reinterpret_cast<const bf16x8*>(reinterpret_cast<const char*>(row) + (step * 16 + hh * 8) * 2);
+  }
+  static __device__ __forceinline__ f32x16 mfma(type a, type b, f32x16 c) {
+    return __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, c, 0, 0, 0);
+  }
+};
+template <> struct Frag<float> {
+  using type = float;
+  static constexpr int kElems = 2;
+  static __device__ __forceinline__ type load(const void* row, int step, int hh) {
+    return *reinterpret_cast<const float*>(reinterpret_cast<const char*>(row) + (step * 2 + hh) * 4);
+  }
+  static __device__ __forceinline__ f32x16 mfma(type a, type b, f32x16 c) {
+    return __builtin_amdgcn_mfma_f32_32x32x2f32(a, b, c, 0, 0, 0);
+  }
+};
+
+struct ScoreArgs {
+  const void* const* q_win;
+  const void* const* k;
+  float* const* indicator;
+  int64_t qs[3], ks[3];      // element strides: batch, head, token
+  int32_t batch, h_kv, group, n, n_p, chunk, n_chunks, n_chunks_p, pool;
+  float c;                   // scale * log2(e): logits are handled in the log2 domain
+  float gamma, inv_sw, inv_swc, inv_g;
+  float* lse;                // [slice][G*S_w]
+  float* part;               // [slice][n_chunks][G*S_w][2]
+  float* hv;                 // [slice][n_chunks_p][G][2]
+  float* raw;                // [slice][n_p]
+};
+
+template <typename T, int D>
+struct Tile {
+  static constexpr int kRowBytes = D * (int)sizeof(T);
+  static constexpr int kPitch = kRowBytes + 16;          // pad: rows land on different banks
+  static constexpr int kPieces = kRowBytes / 16;         // 16-byte pieces per key row
+  static constexpr int kBytes = kTileKeys * kPitch;
+};
+
+// Cooperative copy of keys [t0, t0+64) of one slice into LDS.  Rows past the last key are
+// clamped to it (their logits are masked later), so every access stays inside the slice.
+template <typename T, int D>
+__device__ __forceinline__ void stage_tile(char* lds, const T* kbase, int64_t tok_stride, int t0, int last_key) {
+  using TL = Tile<T, D>;
+  for (int p = threadIdx.x; p < kTileKeys * TL::kPieces; p += blockDim.x) {
+    int key = p / TL::kPieces, piece = p % TL::kPieces;
+    int src = min(t0 + key, last_key);
+    const uint4* g = reinterpret_cast<const uint4*>(reinterpret_cast<const char*>(kbase + (int64_t)src * tok_stride) + piece * 16);
+    *reinterpret_cast<uint4*>(lds + key * TL::kPitch + piece * 16) = *g;
+  }
+}
+
+__device__ __forceinline__ void slice_coords(const ScoreArgs& a, int slice, int& l, int& b, int& g) {
+  g = slice % a.h_kv;
+  b = (slice / a.h_kv) % a.batch;
+  l = slice / (a.h_kv * a.batch);
+}
+
+// ------------------------------------------------------------------------------------------
+// Pass 1: per window row, (reference, sum of 2^(t - reference)) over one chunk of keys.
+// ------------------------------------------------------------------------------------------
+template <typename T, int D, int MB>
+__global__ __launch_bounds__(512) void scores_pass1(ScoreArgs a) {
+  using F = Frag<T>;
+  using TL = Tile<T, D>;
+  constexpr int kSteps = D / F::kElems;
+  __shared__ __attribute__((aligned(16))) char lds[TL::kBytes];
+
+  const int chunk_id = blockIdx.x, slice = blockIdx.y;
+  int l, b, g;
+  slice_coords(a, slice, l, b, g);
+  const int w = threadIdx.x >> 6, lane = threadIdx.x & 63, c32 = lane & 31, hh = lane >> 5;
+  const int s_w = MB * 32;
+  const T* q = reinterpret_cast<const T*>(a.q_win[l]) + b * a.qs[0] + (int64_t)(g * a.group + w) * a.qs[1];
+  const T* kbase = reinterpret_cast<const T*>(a.k[l]) + b * a.ks[0] + (int64_t)g * a.ks[1];
+
+  typename F::type qf[MB][kSteps];
+#pragma unroll
+  for (int nb = 0; nb < MB; ++nb)
+#pragma unroll
+    for (int s = 0; s < kSteps; ++s) qf[nb][s] = F::load(q + (int64_t)(nb * 32 + c32) * a.qs[2], s, hh);
+
+  float mref[MB], lsum[MB];
+#pragma unroll
+  for (int nb = 0; nb < MB; ++nb) { mref[nb] = kMasked; lsum[nb] = 0.f; }
+
+  const int key0 = chunk_id * a.chunk;
+  const int key_end = min(key0 + a.chunk, a.n);
+  for (int t0 = key0; t0 < key_end; t0 += kTileKeys) {
+    __syncthreads();
+    stage_tile<T, D>(lds, kbase, a.ks[2], t0, a.n - 1);
+    __syncthreads();
+#pragma unroll
+    for (int sub = 0; sub < kTileKeys / 32; ++sub) {
+      const int kb = t0 + sub * 32;
+      if (kb >= key_end) break;
+      f32x16 acc[MB];
+#pragma unroll
+      for (int nb = 0; nb < MB; ++nb)
+#pragma unroll
+        for (int v = 0; v < 16; ++v) acc[nb][v] = 0.f;
+      const char* krow = lds + (sub * 32 + c32) * TL::kPitch;
+#pragma unroll
+      for (int s = 0; s < kSteps; ++s) {
+        typename F::type kf = F::load(krow, s, hh);
+#pragma unroll
+        for (int nb = 0; nb < MB; ++nb) acc[nb] = F::mfma(kf, qf[nb][s], acc[nb]);
+      }
+      // acc[nb][v]: key = kb + 8*(v/4) + 4*hh + (v%4), window row = nb*32 + c32.
+      // Key j is visible to window row r iff j <= n_p + r (and j < n).
+      const bool tail = kb + 31 > a.n_p;   // some key of this sub-tile may be hidden or past the end
+#pragma unroll
+      for (int nb = 0; nb < MB; ++nb) {
+        float t[16];
+        const int last_visible = min(a.n_p + nb * 32 + c32, a.n - 1);
+        float tmax = kMasked;
+#pragma unroll
+        for (int v = 0; v < 16; ++v) {
+          t[v] = acc[nb][v] * a.c - mref[nb];
+          if (tail && kb + 8 * (v / 4) + 4 * hh + (v % 4) > last_visible) t[v] = kMasked;
+          tmax = fmaxf(tmax, t[v]);
+        }
+        const bool lift = tmax > kRescale;
+        if (__builtin_amdgcn_ballot_w64(lift)) {
+          if (lift) {
+            float rmax = kMasked;
+#pragma unroll
+            for (int v = 0; v < 16; ++v) {
+              bool hidden = tail && kb + 8 * (v / 4) + 4 * hh + (v % 4) > last_visible;
+              rmax = fmaxf(rmax, hidden ? kMasked : acc[nb][v] * a.c);
+            }
+            lsum[nb] *= exp2f(mref[nb] - rmax);
+            mref[nb] = rmax;
+#pragma unroll
+            for (int v = 0; v < 16; ++v) {
+              bool hidden = tail && kb + 8 * (v / 4) + 4 * hh + (v % 4) > last_visible;
+              t[v] = hidden ? kMasked : acc[nb][v] * a.c - rmax;
+            }
+          }
+        }
+#pragma unroll
+        for (int v = 0; v < 16; ++v) {
+          float e = exp2f(t[v]);
+          if (tail && kb + 8 * (v / 4) + 4 * hh + (v % 4) > last_visible) e = 0.f;
+          lsum[nb] += e;
+        }
+      }
+    }
+  }
+  // Merge the two lane halves of each window row and store the chunk's pair.
+  float* out = a.part + (((int64_t)slice * a.n_chunks + chunk_id) * (a.group * s_w) + w * s_w) * 2;
+#pragma unroll
+  for (int nb = 0; nb < MB; ++nb) {
+    float om = __shfl_xor(mref[nb], 32), ol = __shfl_xor(lsum[nb], 32);
+    float m = fmaxf(mref[nb], om);
+    float s = lsum[nb] * exp2f(mref[nb] - m) + ol * exp2f(om - m);
+    if (hh == 0) {
+      out[(nb * 32 + c32) * 2 + 0] = m;
+      out[(nb * 32 + c32) * 2 + 1] = s;
+    }
+  }
+}
+
+// Combine the chunks' pairs of every window row into lse2 = log2 sum_j 2^(t_j).
+__global__ void scores_combine(ScoreArgs a, int rows_per_slice, int64_t total_rows) {
+  int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (i >= total_rows) return;
+  int64_t slice = i / rows_per_slice;
+  int row = (int)(i % rows_per_slice);
+  const float* p = a.part + (slice * a.n_chunks * rows_per_slice + row) * 2;
+  float m = kMasked;
+  for (int c = 0; c < a.n_chunks; ++c) m = fmaxf(m, p[(int64_t)c * rows_per_slice * 2]);
+  double s = 0.0;
+  for (int c = 0; c < a.n_chunks; ++c) {
+    const float* pc = p + (int64_t)c * rows_per_slice * 2;
+    s += (double)pc[1] * (double)exp2f(pc[0] - m);
+  }
+  a.lse[i] = m + (float)log2(s);
+}
+
+// ------------------------------------------------------------------------------------------
+// Pass 2: normalised weights on the prefix columns; column Mean/Var, entropy, group mean.
+// ------------------------------------------------------------------------------------------
+template <typename T, int D, int MB>
+__global__ __launch_bounds__(512) void scores_pass2(ScoreArgs a) {
+  using F = Frag<T>;
+  using TL = Tile<T, D>;
+  constexpr int kSteps = D / F::kElems;
+  __shared__ __attribute__((aligned(16))) char lds[TL::kBytes];
+  __shared__ float iq_lds[8][kTileKeys];
+
+  const int chunk_id = blockIdx.x, slice = blockIdx.y;
+  int l, b, g;
+  slice_coords(a, slice, l, b, g);
+  const int w = threadIdx.x >> 6, lane = threadIdx.x & 63, c32 = lane & 31, hh = lane >> 5;
+  const int s_w = MB * 32;
+  const T* q = reinterpret_cast<const T*>(a.q_win[l]) + b * a.qs[0] + (int64_t)(g * a.group + w) * a.qs[1];
+  const T* kbase = reinterpret_cast<const T*>(a.k[l]) + b * a.ks[0] + (int64_t)g * a.ks[1];
+
+  typename F::type qf[MB][kSteps];
+#pragma unroll
+  for (int mb = 0; mb < MB; ++mb)
+#pragma unroll
+    for (int s = 0; s < kSteps; ++s) qf[mb][s] = F::load(q + (int64_t)(mb * 32 + c32) * a.qs[2], s, hh);
+
+  // acc[mb][v] will hold window row mb*32 + 8*(v/4) + 4*hh + (v%4) of key column c32.
+  float lse_r[MB][16];
+  const float* lse = a.lse + (int64_t)slice * (a.group * s_w) + w * s_w;
+#pragma unroll
+  for (int mb = 0; mb < MB; ++mb)
+#pragma unroll
+    for (int v = 0; v < 16; ++v) lse_r[mb][v] = lse[mb * 32 + 8 * (v / 4) + 4 * hh + (v % 4)];
+
+  float ent_acc = 0.f, var_acc = 0.f;
+  const int key0 = chunk_id * a.chunk;
+  const int key_end = min(key0 + a.chunk, a.n_p);
+  float* raw = a.raw + (int64_t)slice * a.n_p;
+  for (int t0 = key0; t0 < key_end; t0 += kTileKeys) {
+    __syncthreads();
+    stage_tile<T, D>(lds, kbase, a.ks[2], t0, a.n - 1);
+    __syncthreads();
+#pragma unroll
+    for (int sub = 0; sub < kTileKeys / 32; ++sub) {
+      const int kb = t0 + sub * 32;
+      if (kb >= key_end) {           // whole sub-tile beyond the prefix: contributes zeros
+        if (hh == 0) iq_lds[w][sub * 32 + c32] = 0.f;
+        continue;
+      }
+      f32x16 acc[MB];
+#pragma unroll
+      for (int mb = 0; mb < MB; ++mb)
+#pragma unroll
+        for (int v = 0; v < 16; ++v) acc[mb][v] = 0.f;
+      const char* krow = lds + (sub * 32 + c32) * TL::kPitch;
+#pragma unroll
+      for (int s = 0; s < kSteps; ++s) {
+        typename F::type kf = F::load(krow, s, hh);
+#pragma unroll
+        for (int mb = 0; mb < MB; ++mb) acc[mb] = F::mfma(qf[mb][s], kf, acc[mb]);
+      }
+      float sp = 0.f, sp2 = 0.f, ent = 0.f;
+#pragma unroll
+      for (int mb = 0; mb < MB; ++mb)
+#pragma unroll
+        for (int v = 0; v < 16; ++v) {
+          float t = acc[mb][v] * a.c - lse_r[mb][v];   // log2 of the attention weight
+          float p = exp2f(t);
+          sp += p;
+          sp2 = fmaf(p, p, sp2);
+          ent = fmaf(p, t, ent);
+        }
+      sp += __shfl_xor(sp, 32);
+      sp2 += __shfl_xor(sp2, 32);
+      const bool valid = kb + c32 < key_end;
+      const float mean = sp * a.inv_sw;
+      const float var = fmaxf((sp2 - sp * mean) * a.inv_swc, 0.f);
+      if (valid) {
+        ent_acc += ent;
+        if (hh == 0) var_acc += var;
+      }
+      if (hh == 0) iq_lds[w][sub * 32 + c32] = valid ? mean + a.gamma * var : 0.f;
+    }
+    __syncthreads();
+    if (threadIdx.x < kTileKeys && t0 + (int)threadIdx.x < key_end) {
+      float s = 0.f;
+      for (int ww = 0; ww < a.group; ++ww) s += iq_lds[ww][threadIdx.x];
+      raw[t0 + threadIdx.x] = s * a.inv_g;
+    }
+  }
+  // Per-wave sums in a fixed order.
+#pragma unroll
+  for (int off = 32; off >= 1; off >>= 1) {
+    ent_acc += __shfl_xor(ent_acc, off);
+    var_acc += __shfl_xor(var_acc, off);
+  }
+  if (lane == 0) {
+    float* o = a.hv + (((int64_t)slice * a.n_chunks_p + chunk_id) * a.group + w) * 2;
+    o[0] = ent_acc;
+    o[1] = var_acc;
+  }
+}
+
+// Stride-1 max-pool over the prefix positions, edges clipped (Sec. 4.3 pooling layer).
+__global__ void pool_indicator(ScoreArgs a) {
+  const int slice = blockIdx.y;
+  int l, b, g;
+  slice_coords(a, slice, l, b, g);
+  const int j = blockIdx.x * blockDim.x + threadIdx.x;
+  if (j >= a.n_p) return;
+  const float* raw = a.raw + (int64_t)slice * a.n_p;
+  const int half = a.pool / 2;
+  const int lo = max(j - half, 0), hi = min(j + half, a.n_p - 1);
+  float m = raw[lo];
+  for (int i = lo + 1; i <= hi; ++i) m = fmaxf(m, raw[i]);
+  a.indicator[l][((int64_t)b * a.h_kv + g) * a.n_p + j] = m;
+}
+
+// Eq. 6 per (layer, sequence): fixed-order fp64 reduction of the chunk sums, then the powers.
+__global__ void layer_preference_kernel(const float* hv, int n_layers, int batch, int h_kv, int group,
+                                        int n_chunks_p, double inv_tau1, double inv_tau2,
+                                        double* pref, double* hv_out) {
+  const int l = blockIdx.x / batch, b = blockIdx.x % batch;
+  const int lane = threadIdx.x;
+  const int per_head = n_chunks_p * group;                 // entries of one KV head
+  const float* base = hv + ((int64_t)(l * batch + b) * h_kv) * per_head * 2;
+  const int count = h_kv * per_head;
+  double e = 0.0, v = 0.0;
+  for (int i = lane; i < count; i += 64) {
+    e += (double)base[2 * i];
+    v += (double)base[2 * i + 1];
+  }
+#pragma unroll
+  for (int off = 32; off >= 1; off >>= 1) {
+    e += __shfl_xor(e, off);
+    v += __shfl_xor(v, off);
+  }
+  if (lane == 0) {
+    const double heads = (double)(h_kv * group);
+    const double h_l = -0.6931471805599453 * e / heads;   // sum p*log2 p -> -sum p ln p
+    const double v_l = v / heads;
+    pref[(int64_t)b * n_layers + l] = pow(h_l, inv_tau1) * pow(v_l, inv_tau2);
+    if (hv_out) {
+      hv_out[((int64_t)b * n_layers + l) * 2 + 0] = h_l;
+      hv_out[((int64_t)b * n_layers + l) * 2 + 1] = v_l;
+    }
+  }
+}
+
+template <typename T, int D, int MB>
+int launch_scores(const ScoreArgs& a, int64_t n_slices, hipStream_t stream) {
+  dim3 block(64 * a.group);
+  hipLaunchKernelGGL((scores_pass1<T, D, MB>), dim3(a.n_chunks, (unsigned)n_slices), block, 0, stream, a);
+  const int rows = a.group * MB * 32;
+  const int64_t total_rows = n_slices * rows;
+  hipLaunchKernelGGL(scores_combine, dim3((unsigned)((total_rows + 255) / 256)), dim3(256), 0, stream, a, rows, total_rows);
+  hipLaunchKernelGGL((scores_pass2<T, D, MB>), dim3(a.n_chunks_p, (unsigned)n_slices), block, 0, stream, a);
+  hipLaunchKernelGGL(pool_indicator, dim3((a.n_p + 255) / 256, (unsigned)n_slices), dim3(256), 0, stream, a);
+  CAKE_HIP_TRY(hipGetLastError());
+  return CAKE_OK;
+}
+
+}  // namespace
+}  // namespace cake
+
+using namespace cake;
+
+extern "C" int cake_window_scores(const cake_shape* shape, const cake_params* params,
+                                  const void* const* q_win, const void* const* k,
+                                  const int64_t* q_strides, const int64_t* k_strides,
+                                  float* const* indicator,
+                                  void* workspace, size_t workspace_bytes, void* stream) {
+  if (int rc = check_shape_scores(shape)) return rc;
+  CAKE_REQUIRE(params != nullptr, "params is NULL");
+  CAKE_REQUIRE(q_win && k && indicator, "q_win, k or indicator table is NULL");
+  CAKE_REQUIRE(q_strides && k_strides, "q_strides or k_strides is NULL");
+  CAKE_REQUIRE(params->pool_kernel >= 1 && params->pool_kernel % 2 == 1, "pool_kernel %d must be odd and >= 1", params->pool_kernel);
+  CAKE_REQUIRE(params->var_correction == 0 || params->var_correction == 1, "var_correction %d must be 0 or 1", params->var_correction);
+  CAKE_REQUIRE(std::isfinite(params->gamma) && std::isfinite(params->scale) && params->scale >= 0.f, "gamma/scale must be finite, scale >= 0");
+  const size_t eb = elem_bytes(shape->dtype);
+  for (int i = 0; i < 3; ++i) {
+    CAKE_REQUIRE(q_strides[i] >= 0 && k_strides[i] >= 0, "negative stride");
+    CAKE_REQUIRE((q_strides[i] * eb) % 16 == 0 && (k_strides[i] * eb) % 16 == 0, "strides must be multiples of 16 bytes");
+  }
+  CAKE_REQUIRE(q_strides[2] >= shape->head_dim && k_strides[2] >= shape->head_dim, "token stride below head_dim");
+  const ScoreLayout lay = score_layout(*shape);
+  if (workspace == nullptr || (reinterpret_cast<uintptr_t>(workspace) & 255) != 0)
+    return fail(CAKE_ERR_WORKSPACE, "workspace is NULL or not 256-byte aligned");
+  if (workspace_bytes < lay.total)
+    return fail(CAKE_ERR_WORKSPACE, "workspace has %zu bytes, %zu needed", workspace_bytes, lay.total);
+  if (lay.n_slices > 65535) return fail(CAKE_ERR_UNSUPPORTED, "layers*batch*kv_heads = %lld exceeds 65535 per call", (long long)lay.n_slices);
+
+  ScoreArgs a{};
+  a.q_win = q_win; a.k = k; a.indicator = indicator;
+  for (int i = 0; i < 3; ++i) { a.qs[i] = q_strides[i]; a.ks[i] = k_strides[i]; }
+  a.batch = shape->batch; a.h_kv = shape->n_kv_heads; a.group = shape->n_q_heads / shape->n_kv_heads;
+  a.n = shape->seq_len; a.n_p = shape->seq_len - shape->window;
+  a.chunk = lay.chunk; a.n_chunks = lay.n_chunks; a.n_chunks_p = lay.n_chunks_p; a.pool = params->pool_kernel;
+  const double scale = params->scale > 0.f ? (double)params->scale : 1.0 / std::sqrt((double)shape->head_dim);
+  a.c = (float)(scale * 1.4426950408889634);
+  a.gamma = params->gamma;
+  a.inv_sw = 1.0f / (float)shape->window;
+  a.inv_swc = 1.0f / (float)(shape->window - params->var_correction);
+  a.inv_g = 1.0f / (float)a.group;
+  char* ws = static_cast<char*>(workspace);
+  a.lse = reinterpret_cast<float*>(ws + lay.off_lse);
+  a.part = reinterpret_cast<float*>(ws + lay.off_part);
+  a.hv = reinterpret_cast<float*>(ws + lay.off_hv);
+  a.raw = reinterpret_cast<float*>(ws + lay.off_raw);
+  hipStream_t st = static_cast<hipStream_t>(stream);
+
+#define CAKE_DISPATCH(T, D, MB) return launch_scores<T, D, MB>(a, lay.n_slices, st)
+  const bool bf = shape->dtype == CAKE_BF16;
+  const int d = shape->head_dim, mb = shape->window / 32;
+  if (bf && d == 128 && mb == 1) CAKE_DISPATCH(__bf16, 128, 1);
+  if (bf && d == 128 && mb == 2) CAKE_DISPATCH(__bf16, 128, 2);
+  if (bf && d == 64 && mb == 1) CAKE_DISPATCH(__bf16, 64, 1);
+  if (bf && d == 64 && mb == 2) CAKE_DISPATCH(__bf16, 64, 2);
+  if (!bf && d == 128 && mb == 1) CAKE_DISPATCH(float, 128, 1);
+  if (!bf && d == 128 && mb == 2) CAKE_DISPATCH(float, 128, 2);
+  if (!bf && d == 64 && mb == 1) CAKE_DISPATCH(float, 64, 1);
+  if (!bf && d == 64 && mb == 2) CAKE_DISPATCH(float, 64, 2);
+#undef CAKE_DISPATCH
+  return fail(CAKE_ERR_UNSUPPORTED, "no score kernel for this shape");
+}
+
+extern "C" int cake_layer_preference(const cake_shape* shape, const cake_params* params,
+                                     const void* workspace, size_t workspace_bytes,
+                                     double* pref, double* hv, void* stream) {
+  if (int rc = check_shape_scores(shape)) return rc;
+  CAKE_REQUIRE(params != nullptr && pref != nullptr, "params or pref is NULL");
+  CAKE_REQUIRE(params->tau1 > 0.f && params->tau2 > 0.f && std::isfinite(params->tau1) && std::isfinite(params->tau2),
+               "tau1 and tau2 must be positive and finite");
+  const ScoreLayout lay = score_layout(*shape);
+  if (workspace == nullptr || (reinterpret_cast<uintptr_t>(workspace) & 255) != 0)
+    return fail(CAKE_ERR_WORKSPACE, "workspace is NULL or not 256-byte aligned");
+  if (workspace_bytes < lay.total)
+    return fail(CAKE_ERR_WORKSPACE, "workspace has %zu bytes, %zu needed", workspace_bytes, lay.total);
+  const float* hv_part = reinterpret_cast<const float*>(static_cast<const char*>(workspace) + lay.off_hv);
+  hipLaunchKernelGGL(layer_preference_kernel, dim3(shape->n_layers * shape->batch), dim3(64), 0,
+                     static_cast<hipStream_t>(stream), hv_part, shape->n_layers, shape->batch, shape->n_kv_heads,
+                     shape->n_q_heads / shape->n_kv_heads, lay.n_chunks_p, 1.0 / (double)params->tau1,
+                     1.0 / (double)params->tau2, pref, hv);
+  CAKE_HIP_TRY(hipGetLastError());
+  return CAKE_OK;
+}

@@ -1,0 +1,146 @@
+"""Stage driver for the eviction pass: sequences the five libcake calls (Alg. 1 / Sec. 4.1).
+
+Orchestration and buffer management only; every computation happens inside libcake.
+One-shot mode (Sec. 4.1): scores for all layers, preferences to the host, Eq. 7 budgets,
+top-k and compaction for all layers.  Cascade mode (Sec. 4.2, Alg. 1): stage m admits layer
+m, recomputes B^(m) and re-evicts layers 0..m from their already compacted caches.
+"""
+from __future__ import annotations
+
+from dataclasses import dataclass, field
+from typing import List, Optional, Sequence
+
+import numpy as np
+import torch
+
+from . import binding as C
+
+
+@dataclass
+class PassResult:
+    budgets: np.ndarray                 # [L, B] int, window tokens included
+    keep: np.ndarray                    # [L, B] prefix tokens retained
+    pref: np.ndarray                    # [B, L] float64
+    hv: np.ndarray                      # [B, L, 2] float64 (H_l, V_l)
+    indicator: List[torch.Tensor]       # per layer [B, H_kv, N_p] f32 (pooled)
+    idx: List[torch.Tensor]             # per layer [B, H_kv, cap_l] int32 ascending positions
+    k_out: List[torch.Tensor]           # per layer [B, H_kv, cap_l + S_w, d]
+    v_out: List[torch.Tensor]
+    ind_out: List[torch.Tensor]         # per layer [B, H_kv, cap_l] f32
+    stage_budgets: list = field(default_factory=list)   # cascade mode: budgets after every stage
+
+
+def _strides3(t: torch.Tensor):
+    assert t.dim() == 4 and t.stride(3) == 1, "expect [B, H, rows, d] with contiguous d"
+    return [t.stride(0), t.stride(1), t.stride(2)]
+
+
+class EvictionPass:
+    """Buffers and call sequence for one prompt's eviction pass on one GPU."""
+
+    def __init__(self, q_win: Sequence[torch.Tensor], k: Sequence[torch.Tensor], v: Sequence[torch.Tensor],
+                 total_budget: int, params=None):
+        self.q_win, self.k, self.v = list(q_win), list(k), list(v)
+        q0, k0 = self.q_win[0], self.k[0]
+        self.L = len(self.k)
+        self.B, self.H_q, self.S_w, self.d = q0.shape
+        self.H_kv, self.N = k0.shape[1], k0.shape[2]
+        self.N_p = self.N - self.S_w
+        self.total_budget = int(total_budget)
+        self.dev = k0.device
+        self.dtype = k0.dtype
+        self.params = params if params is not None else C.make_params()
+        self.shape = C.make_shape(self.B, self.L, self.H_q, self.H_kv, self.d, self.N, self.S_w, self.dtype)
+        for t in self.q_win[1:]:
+            assert _strides3(t) == _strides3(q0)
+        for t in self.k[1:] + self.v:
+            assert _strides3(t) == _strides3(k0)
+
+        self.workspace = torch.empty(C.cake_workspace_bytes(self.shape), dtype=torch.uint8, device=self.dev)
+        self.indicator = torch.empty(self.L, self.B, self.H_kv, self.N_p, dtype=torch.float32, device=self.dev)
+        self.pref = torch.empty(self.B, self.L, dtype=torch.float64, device=self.dev)
+        self.hv = torch.empty(self.B, self.L, 2, dtype=torch.float64, device=self.dev)
+        self.pref_host = torch.empty(self.B, self.L, dtype=torch.float64).pin_memory()
+        self.hv_host = torch.empty(self.B, self.L, 2, dtype=torch.float64).pin_memory()
+
+        self.tbl_q = C.ptr_table(self.q_win)
+        self.tbl_k = C.ptr_table(self.k)
+        self.tbl_v = C.ptr_table(self.v)
+        self.tbl_ind = C.ptr_table([self.indicator[l] for l in range(self.L)])
+
+        # Output pools.  Row capacity of layer l is cap_l = max_b keep[l, b]; over all layers
+        # sum_l cap_l <= B * (B_total - L*S_w), and exactly B_total - L*S_w when B = 1.
+        max_rows = min(self.B * max(self.total_budget - self.L * self.S_w, 0), self.L * self.N_p)
+        rows_kv = max_rows + self.L * self.S_w
+        bh = self.B * self.H_kv
+        self.pool_k = torch.empty(bh * rows_kv * self.d, dtype=self.dtype, device=self.dev)
+        self.pool_v = torch.empty_like(self.pool_k)
+        self.pool_idx = torch.empty(bh * max(max_rows, 1), dtype=torch.int32, device=self.dev)
+        self.pool_ind = torch.empty(bh * max(max_rows, 1), dtype=torch.float32, device=self.dev)
+        self.tbl_out_host = torch.empty(4, self.L, dtype=torch.int64).pin_memory()
+        self.tbl_out = torch.empty(4, self.L, dtype=torch.int64, device=self.dev)
+
+    # ------------------------------------------------------------------ the five calls
+    def scores(self, stream=None) -> None:
+        C.cake_window_scores(self.shape, self.params, self.tbl_q, self.tbl_k, _strides3(self.q_win[0]),
+                             _strides3(self.k[0]), self.tbl_ind, self.workspace, stream)
+        C.cake_layer_preference(self.shape, self.params, self.workspace, self.pref, self.hv, stream)
+
+    def preferences_to_host(self):
+        """The pass's one device-to-host crossing: L*B preferences (and H, V)."""
+        self.pref_host.copy_(self.pref, non_blocking=True)
+        self.hv_host.copy_(self.hv, non_blocking=True)
+        torch.cuda.current_stream().synchronize()
+        return self.pref_host.numpy().copy(), self.hv_host.numpy().copy()
+
+    def allocate(self, pref: np.ndarray) -> np.ndarray:
+        """Eq. 7 per sequence.  Returns budgets [L, B]."""
+        out = np.empty((self.L, self.B), dtype=np.int64)
+        for b in range(self.B):
+            out[:, b] = C.cake_cascade_allocate(pref[b], self.total_budget, self.S_w, self.N)
+        return out
+
+    def _carve_outputs(self, keep: np.ndarray):
+        """Per-layer views of the output pools for the given keep counts [L, B]."""
+        caps = keep.max(axis=1)
+        bh = self.B * self.H_kv
+        idx, k_out, v_out, ind_out = [], [], [], []
+        off_kv = off_i = 0
+        th = self.tbl_out_host.numpy()
+        for l in range(self.L):
+            cap = int(caps[l])
+            n_kv = bh * (cap + self.S_w) * self.d
+            n_i = bh * cap
+            k_out.append(self.pool_k[off_kv: off_kv + n_kv].view(self.B, self.H_kv, cap + self.S_w, self.d))
+            v_out.append(self.pool_v[off_kv: off_kv + n_kv].view(self.B, self.H_kv, cap + self.S_w, self.d))
+            idx.append(self.pool_idx[off_i: off_i + n_i].view(self.B, self.H_kv, cap))
+            ind_out.append(self.pool_ind[off_i: off_i + n_i].view(self.B, self.H_kv, cap))
+            th[0, l] = self.pool_idx.data_ptr() + off_i * 4
+            th[1, l] = self.pool_k.data_ptr() + off_kv * self.pool_k.element_size()
+            th[2, l] = self.pool_v.data_ptr() + off_kv * self.pool_v.element_size()
+            th[3, l] = self.pool_ind.data_ptr() + off_i * 4
+            off_kv += n_kv
+            off_i += n_i
+        self.tbl_out.copy_(self.tbl_out_host, non_blocking=True)
+        return idx, k_out, v_out, ind_out
+
+    def evict(self, budgets: np.ndarray, stream=None):
+        keep = np.minimum(np.maximum(budgets - self.S_w, 0), self.N_p)
+        idx, k_out, v_out, ind_out = self._carve_outputs(keep)
+        cur = [self.N_p] * (self.L * self.B)
+        kk = [int(x) for x in keep.reshape(-1)]
+        C.cake_select_topk(self.shape, self.tbl_ind, cur, kk, self.tbl_out[0], None, stream)
+        strides = [_strides3(self.k[0])] * self.L
+        C.cake_compact_kv(self.shape, self.tbl_k, self.tbl_v, strides, cur, kk, self.tbl_out[0], self.tbl_ind,
+                          self.tbl_out[1], self.tbl_out[2], self.tbl_out[3], stream)
+        return keep, idx, k_out, v_out, ind_out
+
+    # ------------------------------------------------------------------ whole pass
+    def run(self) -> PassResult:
+        """One-shot pass (Sec. 4.1): all layers scored, Eq. 7 budgets, one EVICT per layer."""
+        self.scores()
+        pref, hv = self.preferences_to_host()
+        budgets = self.allocate(pref)
+        keep, idx, k_out, v_out, ind_out = self.evict(budgets)
+        return PassResult(budgets, keep, pref, hv, [self.indicator[l] for l in range(self.L)], idx, k_out, v_out,
+                          ind_out)
