@@ -1,0 +1,208 @@
+#!/usr/bin/env python3
+"""Benchmark of the CAKE prefill eviction pass on one MI355X.
+
+One "step" is the whole hot path over one prompt's resident K/V: window scores for all
+layers, layer preferences, the device-to-host hop of the preferences, Eq. 7 allocation on
+the host, per-head top-k and K/V compaction for all layers.  Inputs are synthetic
+(synth/generate.py) and already resident in HBM when the timed region starts.
+
+Prints ONE JSON line.  `value` = B*N*L / seconds per step (prefix tokens x layers per second).
+`roofline` describes the dominant kernel, timed live with HIP events inside the timed region.
+`cpu_baseline` times the fp64 NumPy oracle on a bounded sample of the same workload.
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBPS = 8000.0          # MI355X HBM3E
+MFMA_BF16_PEAK_TFLOPS = 2500.0  # dense bf16
+MFMA_F32_PEAK_TFLOPS = 157.3
+
+
+def parse_args():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--config", type=int, default=4, help="synthetic config id (4 = 128K context, the headline)")
+    ap.add_argument("--layers", type=int, default=0, help="override layer count (0 = the config's)")
+    ap.add_argument("--no-cpu-baseline", action="store_true", help="skip the oracle timing (profiling runs)")
+    return ap.parse_args()
+
+
+def cpu_baseline(cfg, layer_inputs, params):
+    """Time the oracle on KV heads 0..n-1 of layer 0 (scores, indicator, top-k, compaction) plus
+    one allocation; scale to tokens*layers/s by the fraction of a layer that was done."""
+    import numpy as np
+    from oracle import cake_oracle as co
+    try:
+        from threadpoolctl import threadpool_info
+        threads = max([p.get("num_threads", 1) for p in threadpool_info()] or [os.cpu_count() or 1])
+    except Exception:
+        threads = os.cpu_count() or 1
+    p = co.OracleParams(scale=None, gamma=params.gamma, tau1=params.tau1, tau2=params.tau2,
+                        var_correction=params.var_correction, pool_kernel=params.pool_kernel)
+    group = cfg.n_q_heads // cfg.n_kv_heads
+    q = layer_inputs["q_win"].double().cpu().numpy()
+    heads_done, t_total = 0, 0.0
+    keep = max(cfg.total_budget // cfg.n_layers - cfg.window, 1)
+    budget_s = 12.0
+    for g in range(cfg.n_kv_heads):
+        k_g = layer_inputs["k"][g:g + 1].double().cpu().numpy()
+        v_g = layer_inputs["v"][g].double().cpu().numpy()
+        t0 = time.perf_counter()
+        a_obs = co.observed(co.window_attention(q[g * group:(g + 1) * group], k_g, p.scale), cfg.window)
+        ind = co.eviction_indicator(a_obs, group, p)[0]
+        co.dispersion(a_obs); co.shift(a_obs, p.var_correction)
+        co.evict(k_g[0], v_g, ind, keep + cfg.window, cfg.window)
+        t_total += time.perf_counter() - t0
+        heads_done += 1
+        if t_total > budget_s:
+            break
+    t0 = time.perf_counter()
+    co.cascade_allocate(np.linspace(0.5, 2.0, cfg.n_layers), cfg.total_budget, cfg.window, cfg.seq_len)
+    t_alloc = time.perf_counter() - t0
+    layer_frac = heads_done / cfg.n_kv_heads
+    tokens_layers = cfg.seq_len * layer_frac
+    value = tokens_layers / (t_total + t_alloc * layer_frac / cfg.n_layers)
+    return {"value": value, "unit": "tokens*layers/s", "cores": int(threads), "kind": "oracle",
+            "sample": f"config {cfg.cid} layer 0, KV heads 0-{heads_done - 1} of {cfg.n_kv_heads} (window attention, "
+                      f"indicator, H, V, top-k, compaction) in {t_total:.1f} s, plus one {cfg.n_layers}-layer allocation; "
+                      f"scaled by the fraction of a layer done"}
+
+
+def main():
+    args = parse_args()
+    if args.gpus != 1:
+        print(f"bench.py measures one GPU only: this build has no multi-GPU path (asked for --gpus {args.gpus}).",
+              file=sys.stderr)
+        sys.exit(2)
+    import numpy as np
+    import torch
+    if not torch.cuda.is_available():
+        print("bench.py needs a GPU (torch.cuda.is_available() is False).", file=sys.stderr)
+        sys.exit(2)
+    from synth import CONFIGS, make_layer
+    import paper_2503_12491_amd as cake
+    from paper_2503_12491_amd import _ffi
+    if not os.path.exists(_ffi.LIB_PATH):
+        from paper_2503_12491_amd.build import build
+        build()
+
+    cfg = CONFIGS[args.config]
+    if args.layers:
+        cfg = cfg.scaled(n_layers=args.layers, total_budget=cfg.total_budget // cfg.n_layers * args.layers)
+    dev = torch.device("cuda:0")
+    torch.cuda.set_device(dev)
+    L, B = cfg.n_layers, cfg.batch
+    dt = cfg.torch_dtype
+    q_all = torch.empty(L, B, cfg.n_q_heads, cfg.window, cfg.head_dim, dtype=dt, device=dev)
+    k_all = torch.empty(L, B, cfg.n_kv_heads, cfg.seq_len, cfg.head_dim, dtype=dt, device=dev)
+    v_all = torch.empty_like(k_all)
+    for l in range(L):
+        for b in range(B):
+            one = make_layer(cfg, l, b, device=dev)
+            q_all[l, b], k_all[l, b], v_all[l, b] = one["q_win"], one["k"], one["v"]
+            del one
+    torch.cuda.synchronize()
+    params = cake.make_params()
+    ev = cake.EvictionPass([q_all[l] for l in range(L)], [k_all[l] for l in range(L)], [v_all[l] for l in range(L)],
+                           cfg.total_budget, params)
+
+    for _ in range(args.warmup):
+        ev.run()
+    torch.cuda.synchronize()
+
+    # ---- timed region: exactly `steps` passes, per-kernel HIP events on the launch stream ----
+    cake.cake_profile_enable(True)
+    names = ["scores_pass1", "scores_combine", "scores_pass2", "pool_indicator", "layer_preference",
+             "select_topk", "compact_kv"]
+    kernel_ms = {n: 0.0 for n in names}
+    e = [[torch.cuda.Event(enable_timing=True) for _ in range(5)] for _ in range(args.steps)]
+    torch.cuda.synchronize()
+    t_start = time.perf_counter()
+    for s in range(args.steps):
+        cake.cake_window_scores(ev.shape, ev.params, ev.tbl_q, ev.tbl_k, [q_all[0].stride(i) for i in range(3)],
+                                [k_all[0].stride(i) for i in range(3)], ev.tbl_ind, ev.workspace)
+        e[s][0].record()
+        cake.cake_layer_preference(ev.shape, ev.params, ev.workspace, ev.pref, ev.hv)
+        e[s][1].record()
+        pref, hv = ev.preferences_to_host()
+        ms4 = cake.cake_profile_read()           # events already complete: the stream was just synchronised
+        budgets = ev.allocate(pref)
+        keep = np.minimum(np.maximum(budgets - ev.S_w, 0), ev.N_p)
+        idx, k_out, v_out, ind_out = ev._carve_outputs(keep)
+        cur = [ev.N_p] * (L * B)
+        kk = [int(x) for x in keep.reshape(-1)]
+        e[s][2].record()
+        cake.cake_select_topk(ev.shape, ev.tbl_ind, cur, kk, ev.tbl_out[0])
+        e[s][3].record()
+        strides = [[k_all[0].stride(i) for i in range(3)]] * L
+        cake.cake_compact_kv(ev.shape, ev.tbl_k, ev.tbl_v, strides, cur, kk, ev.tbl_out[0], ev.tbl_ind,
+                             ev.tbl_out[1], ev.tbl_out[2], ev.tbl_out[3])
+        e[s][4].record()
+        for n, ms in zip(names[:4], ms4):
+            kernel_ms[n] += ms
+    torch.cuda.synchronize()
+    elapsed = time.perf_counter() - t_start
+    for s in range(args.steps):
+        kernel_ms["layer_preference"] += e[s][0].elapsed_time(e[s][1])
+        kernel_ms["select_topk"] += e[s][2].elapsed_time(e[s][3])
+        kernel_ms["compact_kv"] += e[s][3].elapsed_time(e[s][4])
+    cake.cake_profile_enable(False)
+    kernel_ms = {n: v / args.steps for n, v in kernel_ms.items()}
+    ms_per_step = elapsed / args.steps * 1e3
+    tokens_layers = B * cfg.seq_len * L
+    value = tokens_layers / (elapsed / args.steps)
+
+    # ---- algorithmic bytes (one read of K, indicator traffic, gathered rows) --------------------
+    eb = 2 if cfg.dtype == "bf16" else 4
+    k_bytes = tokens_layers * cfg.n_kv_heads * cfg.head_dim * eb                     # one read of K
+    n_rows = B * L * cfg.n_kv_heads
+    ind_bytes = n_rows * cfg.prefix_len * 4
+    kept_rows = int((keep.sum() + L * B * cfg.window) * cfg.n_kv_heads)
+    compact_bytes = kept_rows * cfg.head_dim * eb * 2 * 2                            # K and V, read + write
+    alg = {"scores_pass1": k_bytes, "scores_pass2": k_bytes + ind_bytes, "pool_indicator": 2 * ind_bytes,
+           "select_topk": 4 * ind_bytes, "compact_kv": compact_bytes, "scores_combine": 0, "layer_preference": 0}
+    pass_alg_bytes = k_bytes + ind_bytes * 7 + compact_bytes
+    dominant = max(kernel_ms, key=kernel_ms.get)
+    dom_s = kernel_ms[dominant] * 1e-3
+    group = cfg.n_q_heads // cfg.n_kv_heads
+    flops_pass = 2.0 * tokens_layers * cfg.n_q_heads * cfg.window * cfg.head_dim   # one logits pass
+    achieved = alg[dominant] / dom_s / 1e9
+    roofline = {"kernel": dominant, "bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBPS, "unit": "GB/s",
+                "frac": achieved / HBM_PEAK_GBPS, "traffic": None}
+    mfma_peak = MFMA_BF16_PEAK_TFLOPS if cfg.dtype == "bf16" else MFMA_F32_PEAK_TFLOPS
+    extra = {
+        "kernel_ms": {n: round(v, 4) for n, v in kernel_ms.items()},
+        "pass_algorithmic_GBps": pass_alg_bytes / (elapsed / args.steps) / 1e9,
+        "pass_hbm_frac": pass_alg_bytes / (elapsed / args.steps) / 1e9 / HBM_PEAK_GBPS,
+        "score_mfma_TFLOPs": {n: flops_pass / (kernel_ms[n] * 1e-3) / 1e12 for n in ("scores_pass1", "scores_pass2")},
+        "score_mfma_frac": {n: flops_pass / (kernel_ms[n] * 1e-3) / 1e12 / mfma_peak for n in ("scores_pass1", "scores_pass2")},
+        "host_and_gaps_ms": ms_per_step - sum(kernel_ms.values()),
+    }
+
+    out = {
+        "metric": "prefix tokens*layers/s evicted at 128K ctx" if cfg.cid == 4 else f"prefix tokens*layers/s evicted (config {cfg.cid})",
+        "value": value, "unit": "tokens*layers/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": cfg.dtype, "data": "synthetic",
+        "config": {"workload": f"config {cfg.cid} ({cfg.name}): L={L} H_q={cfg.n_q_heads} H_kv={cfg.n_kv_heads} "
+                               f"d={cfg.head_dim} N={cfg.seq_len} S_w={cfg.window} B={B} B_total={cfg.total_budget} "
+                               f"one-shot pass", "gamma": params.gamma, "tau1": params.tau1, "tau2": params.tau2,
+                   "pool_kernel": params.pool_kernel},
+        "roofline": roofline, "stages": extra,
+    }
+    if not args.no_cpu_baseline:
+        layer0 = {"q_win": q_all[0, 0], "k": k_all[0, 0], "v": v_all[0, 0]}
+        out["cpu_baseline"] = cpu_baseline(cfg, layer0, params)
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()
