@@ -180,6 +180,17 @@ int cake_compact_kv(const cake_shape* shape,
                     void* const* k_out, void* const* v_out, float* const* ind_out,
                     void* stream);
 
+/*
+ * Diagnostics, not part of the method: per-kernel timing of cake_window_scores.
+ * While enabled, every cake_window_scores call records HIP events on its stream around its
+ * kernels (a few microseconds of overhead).  cake_profile_read waits for the last recorded
+ * event and returns milliseconds of the most recent call: ms[0] pass 1 (row normalisers),
+ * ms[1] combine, ms[2] pass 2 (column statistics), ms[3] pooling.  Process-wide state, not
+ * thread-safe; events are created on first use and destroyed by cake_profile_enable(0).
+ */
+int cake_profile_enable(int enable);
+int cake_profile_read(float* ms /* host [4], out */);
+
 #ifdef __cplusplus
 }
 #endif

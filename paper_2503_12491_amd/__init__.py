@@ -5,6 +5,6 @@ arithmetic runs in the HIP kernels.  There is no CPU or PyTorch fallback: callin
 anything without a built libcake.so raises.
 """
 from .binding import (CAKE_BF16, CAKE_F32, CakeError, cake_cascade_allocate, cake_compact_kv,  # noqa: F401
-                      cake_layer_preference, cake_select_topk, cake_version, cake_window_scores,
+                      cake_layer_preference, cake_profile_enable, cake_profile_read, cake_select_topk, cake_version, cake_window_scores,
                       cake_workspace_bytes, make_params, make_shape, ptr_table)
 from .driver import EvictionPass, PassResult  # noqa: F401

@@ -34,6 +34,8 @@ _SIGNATURES = {
     "cake_compact_kv": (ctypes.c_int, [ctypes.POINTER(cake_shape), _P, _P, ctypes.POINTER(ctypes.c_int64),
                                        ctypes.POINTER(ctypes.c_int32), ctypes.POINTER(ctypes.c_int32), _P, _P,
                                        _P, _P, _P, _P]),
+    "cake_profile_enable": (ctypes.c_int, [ctypes.c_int]),
+    "cake_profile_read": (ctypes.c_int, [ctypes.POINTER(ctypes.c_float)]),
 }
 
 _lib = None

@@ -104,3 +104,14 @@ def cake_compact_kv(shape, k_in, v_in, kv_strides, cur_len, k, idx, ind_in, k_ou
     _check(load().cake_compact_kv(ctypes.byref(shape), _ptr(k_in), _ptr(v_in), _i64(flat), _i32(cur_len), _i32(k),
                                   _ptr(idx), _ptr(ind_in), _ptr(k_out), _ptr(v_out), _ptr(ind_out),
                                   _stream(stream)))
+
+
+def cake_profile_enable(enable: bool) -> None:
+    _check(load().cake_profile_enable(1 if enable else 0))
+
+
+def cake_profile_read() -> list:
+    """Milliseconds of the last cake_window_scores call: [pass 1, combine, pass 2, pooling]."""
+    out = (ctypes.c_float * 4)()
+    _check(load().cake_profile_read(out))
+    return list(out)

@@ -371,15 +371,32 @@ __global__ void layer_preference_kernel(const float* hv, int n_layers, int batch
   }
 }
 
+// Optional event timing of the four kernels (diagnostics).
+struct Profile {
+  bool enabled = false, recorded = false, created = false;
+  hipEvent_t ev[5] = {};
+};
+Profile g_profile;
+
+inline void mark(int i, hipStream_t stream) {
+  if (g_profile.enabled && g_profile.created) (void)hipEventRecord(g_profile.ev[i], stream);
+}
+
 template <typename T, int D, int MB>
 int launch_scores(const ScoreArgs& a, int64_t n_slices, hipStream_t stream) {
   dim3 block(64 * a.group);
+  mark(0, stream);
   hipLaunchKernelGGL((scores_pass1<T, D, MB>), dim3(a.n_chunks, (unsigned)n_slices), block, 0, stream, a);
+  mark(1, stream);
   const int rows = a.group * MB * 32;
   const int64_t total_rows = n_slices * rows;
   hipLaunchKernelGGL(scores_combine, dim3((unsigned)((total_rows + 255) / 256)), dim3(256), 0, stream, a, rows, total_rows);
+  mark(2, stream);
   hipLaunchKernelGGL((scores_pass2<T, D, MB>), dim3(a.n_chunks_p, (unsigned)n_slices), block, 0, stream, a);
+  mark(3, stream);
   hipLaunchKernelGGL(pool_indicator, dim3((a.n_p + 255) / 256, (unsigned)n_slices), dim3(256), 0, stream, a);
+  mark(4, stream);
+  if (g_profile.enabled && g_profile.created) g_profile.recorded = true;
   CAKE_HIP_TRY(hipGetLastError());
   return CAKE_OK;
 }
@@ -388,6 +405,28 @@ int launch_scores(const ScoreArgs& a, int64_t n_slices, hipStream_t stream) {
 }  // namespace cake
 
 using namespace cake;
+
+extern "C" int cake_profile_enable(int enable) {
+  if (enable && !g_profile.created) {
+    for (auto& e : g_profile.ev) CAKE_HIP_TRY(hipEventCreate(&e));
+    g_profile.created = true;
+  }
+  if (!enable && g_profile.created) {
+    for (auto& e : g_profile.ev) (void)hipEventDestroy(e);
+    g_profile.created = false;
+    g_profile.recorded = false;
+  }
+  g_profile.enabled = enable != 0;
+  return CAKE_OK;
+}
+
+extern "C" int cake_profile_read(float* ms) {
+  CAKE_REQUIRE(ms != nullptr, "ms is NULL");
+  CAKE_REQUIRE(g_profile.enabled && g_profile.recorded, "no profiled cake_window_scores call to read");
+  CAKE_HIP_TRY(hipEventSynchronize(g_profile.ev[4]));
+  for (int i = 0; i < 4; ++i) CAKE_HIP_TRY(hipEventElapsedTime(&ms[i], g_profile.ev[i], g_profile.ev[i + 1]));
+  return CAKE_OK;
+}
 
 extern "C" int cake_window_scores(const cake_shape* shape, const cake_params* params,
                                   const void* const* q_win, const void* const* k,
