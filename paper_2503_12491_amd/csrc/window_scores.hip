@@ -19,8 +19,11 @@
 //   pref    fixed-order fp64 reduction of the per-chunk entropy/variance sums    -> P_l, H_l, V_l
 //
 // One workgroup = G wavefronts = one chunk of keys of one slice; wave w serves query head
-// g*G + w.  K tiles of 64 keys are staged through LDS once per workgroup and shared by the G
-// waves.  Everything is deterministic: no float atomics, fixed reduction orders.
+// g*G + w.  K tiles of 64 keys go from global memory straight into LDS (global_load_lds, 16
+// bytes per lane), double-buffered so that tile t+1 is in flight while tile t is consumed, and
+// are shared by the G waves.  Rows are stored unpadded with their 16-byte pieces XOR-swizzled by
+// the row index so that the MFMA operand reads spread over the banks.
+// Everything is deterministic: no float atomics, fixed reduction orders.
 #include <cmath>
 
 #include "cake_internal.h"
@@ -30,10 +33,24 @@ namespace {
 
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef float f32x16 __attribute__((ext_vector_type(16)));
+typedef __attribute__((address_space(1))) const void* global_cptr;
+typedef __attribute__((address_space(3))) void* lds_ptr;
 
 constexpr int kTileKeys = 64;        // keys staged per LDS tile (two 32-key MFMA sub-tiles)
 constexpr float kMasked = -1.0e30f;  // stands for -inf without producing NaN in differences
 constexpr float kRescale = 40.0f;    // pass 1 re-references a row when a logit exceeds it by 2^40
+
+__device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }  // v_exp_f32
+
+template <typename T, int D>
+struct Tile {
+  static constexpr int kRowBytes = D * (int)sizeof(T);
+  static constexpr int kPieces = kRowBytes / 16;         // 16-byte pieces per key row (power of two)
+  static constexpr int kBytes = kTileKeys * kRowBytes;
+  static constexpr int kGroups = kBytes / 1024;          // one wave-wide 1 KiB transfer each
+  // LDS byte offset of piece q of row r: pieces are permuted within the row by r.
+  static __device__ __forceinline__ int offset(int r, int q) { return r * kRowBytes + ((q ^ (r & (kPieces - 1))) << 4); }
+};
 
 // MFMA operand fragments.  For both the A and the B operand of the 32x32 instructions lane
 // (c32, hh) supplies, for its row/column c32, a group of consecutive reduction elements chosen
@@ -42,8 +59,12 @@ template <typename T> struct Frag;
 template <> struct Frag<__bf16> {
   using type = bf16x8;
   static constexpr int kElems = 16;  // reduction elements per MFMA
-  static __device__ __forceinline__ type load(const void* row, int step, int hh) {
-    return *reinterpret_cast<const bf16x8*>(reinterpret_cast<const char*>(row) + (step * 16 + hh * 8) * 2);
+  static __device__ __forceinline__ type load_global(const __bf16* row, int step, int hh) {
+    return *reinterpret_cast<const bf16x8*>(row + step * 16 + hh * 8);
+  }
+  template <typename TL>
+  static __device__ __forceinline__ type load_lds(const char* tile, int r, int step, int hh) {
+    return *reinterpret_cast<const bf16x8*>(tile + TL::offset(r, 2 * step + hh));
   }
   static __device__ __forceinline__ f32x16 mfma(type a, type b, f32x16 c) {
     return __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, c, 0, 0, 0);
@@ -52,8 +73,11 @@ template <> struct Frag<__bf16> {
 template <> struct Frag<float> {
   using type = float;
   static constexpr int kElems = 2;
-  static __device__ __forceinline__ type load(const void* row, int step, int hh) {
-    return *reinterpret_cast<const float*>(reinterpret_cast<const char*>(row) + (step * 2 + hh) * 4);
+  static __device__ __forceinline__ type load_global(const float* row, int step, int hh) { return row[step * 2 + hh]; }
+  template <typename TL>
+  static __device__ __forceinline__ type load_lds(const char* tile, int r, int step, int hh) {
+    const int e = step * 2 + hh;
+    return *reinterpret_cast<const float*>(tile + TL::offset(r, e >> 2) + (e & 3) * 4);
   }
   static __device__ __forceinline__ f32x16 mfma(type a, type b, f32x16 c) {
     return __builtin_amdgcn_mfma_f32_32x32x2f32(a, b, c, 0, 0, 0);
@@ -74,26 +98,25 @@ struct ScoreArgs {
   float* raw;                // [slice][n_p]
 };
 
+// Start the transfer of keys [t0, t0+64) of one slice into an LDS tile.  Each wave issues
+// whole 1 KiB groups; lane i of a group fills LDS bytes [16 i, 16 i + 16) of that group and
+// fetches the piece of the key row that the swizzle assigns to that place.  Rows past the last
+// key are clamped to it (their logits are masked later), so every access stays inside the slice.
 template <typename T, int D>
-struct Tile {
-  static constexpr int kRowBytes = D * (int)sizeof(T);
-  static constexpr int kPitch = kRowBytes + 16;          // pad: rows land on different banks
-  static constexpr int kPieces = kRowBytes / 16;         // 16-byte pieces per key row
-  static constexpr int kBytes = kTileKeys * kPitch;
-};
-
-// Cooperative copy of keys [t0, t0+64) of one slice into LDS.  Rows past the last key are
-// clamped to it (their logits are masked later), so every access stays inside the slice.
-template <typename T, int D>
-__device__ __forceinline__ void stage_tile(char* lds, const T* kbase, int64_t tok_stride, int t0, int last_key) {
+__device__ __forceinline__ void issue_tile(char* tile, const char* kbase, int64_t tok_bytes, int t0, int last_key,
+                                           int wave, int n_waves, int lane) {
   using TL = Tile<T, D>;
-  for (int p = threadIdx.x; p < kTileKeys * TL::kPieces; p += blockDim.x) {
-    int key = p / TL::kPieces, piece = p % TL::kPieces;
-    int src = min(t0 + key, last_key);
-    const uint4* g = reinterpret_cast<const uint4*>(reinterpret_cast<const char*>(kbase + (int64_t)src * tok_stride) + piece * 16);
-    *reinterpret_cast<uint4*>(lds + key * TL::kPitch + piece * 16) = *g;
+  for (int i = wave; i < TL::kGroups; i += n_waves) {
+    const int off = i * 1024 + lane * 16;
+    const int r = off / TL::kRowBytes, slot = (off % TL::kRowBytes) >> 4;
+    const int q = slot ^ (r & (TL::kPieces - 1));
+    const char* src = kbase + (int64_t)min(t0 + r, last_key) * tok_bytes + q * 16;
+    __builtin_amdgcn_global_load_lds((global_cptr)src, (lds_ptr)(tile + i * 1024), 16, 0, 0);
   }
 }
+
+// All of this wave's outstanding vector-memory operations (the tile transfers) have landed.
+__device__ __forceinline__ void wait_vmem() { __builtin_amdgcn_s_waitcnt(0x0F70); }   // vmcnt(0)
 
 __device__ __forceinline__ void slice_coords(const ScoreArgs& a, int slice, int& l, int& b, int& g) {
   g = slice % a.h_kv;
@@ -101,104 +124,134 @@ __device__ __forceinline__ void slice_coords(const ScoreArgs& a, int slice, int&
   l = slice / (a.h_kv * a.batch);
 }
 
+template <typename T, int D, int MB>
+__device__ __forceinline__ void load_q(typename Frag<T>::type (&qf)[MB][D / Frag<T>::kElems], const T* q,
+                                       int64_t tok_stride, int c32, int hh) {
+  using F = Frag<T>;
+#pragma unroll
+  for (int mb = 0; mb < MB; ++mb)
+#pragma unroll
+    for (int s = 0; s < D / F::kElems; ++s) qf[mb][s] = F::load_global(q + (int64_t)(mb * 32 + c32) * tok_stride, s, hh);
+}
+
 // ------------------------------------------------------------------------------------------
 // Pass 1: per window row, (reference, sum of 2^(t - reference)) over one chunk of keys.
 // ------------------------------------------------------------------------------------------
+template <typename T, int D, int MB, bool kTail>
+__device__ __forceinline__ void pass1_subtile(const char* tile, int sub, int kb,
+                                              const typename Frag<T>::type (&qf)[MB][D / Frag<T>::kElems],
+                                              float (&mref)[MB], float (&lsum)[MB], float c, int n, int n_p,
+                                              int c32, int hh) {
+  using F = Frag<T>;
+  using TL = Tile<T, D>;
+  constexpr int kSteps = D / F::kElems;
+  f32x16 acc[MB];
+#pragma unroll
+  for (int nb = 0; nb < MB; ++nb)
+#pragma unroll
+    for (int v = 0; v < 16; ++v) acc[nb][v] = 0.f;
+#pragma unroll
+  for (int s = 0; s < kSteps; ++s) {
+    typename F::type kf = F::template load_lds<TL>(tile, sub * 32 + c32, s, hh);
+#pragma unroll
+    for (int nb = 0; nb < MB; ++nb) acc[nb] = F::mfma(kf, qf[nb][s], acc[nb]);
+  }
+  // acc[nb][v]: key = kb + 8*(v/4) + 4*hh + (v%4), window row = nb*32 + c32.
+  // Key j is visible to window row r iff j <= n_p + r (and j < n).
+#pragma unroll
+  for (int nb = 0; nb < MB; ++nb) {
+    const int last_visible = min(n_p + nb * 32 + c32, n - 1);
+    float t[16];
+    float tmax = kMasked;
+#pragma unroll
+    for (int v = 0; v < 16; ++v) {
+      t[v] = acc[nb][v] * c - mref[nb];
+      if (kTail && kb + 8 * (v / 4) + 4 * hh + (v % 4) > last_visible) t[v] = kMasked;
+      tmax = fmaxf(tmax, t[v]);
+    }
+    const bool lift = tmax > kRescale;
+    if (__builtin_amdgcn_ballot_w64(lift)) {
+      if (lift) {
+        float rmax = kMasked;
+#pragma unroll
+        for (int v = 0; v < 16; ++v) {
+          const bool hidden = kTail && kb + 8 * (v / 4) + 4 * hh + (v % 4) > last_visible;
+          rmax = fmaxf(rmax, hidden ? kMasked : acc[nb][v] * c);
+        }
+        lsum[nb] *= fast_exp2(mref[nb] - rmax);
+        mref[nb] = rmax;
+#pragma unroll
+        for (int v = 0; v < 16; ++v) {
+          const bool hidden = kTail && kb + 8 * (v / 4) + 4 * hh + (v % 4) > last_visible;
+          t[v] = hidden ? kMasked : acc[nb][v] * c - rmax;
+        }
+      }
+    }
+#pragma unroll
+    for (int v = 0; v < 16; ++v) {
+      float e = fast_exp2(t[v]);
+      if (kTail && kb + 8 * (v / 4) + 4 * hh + (v % 4) > last_visible) e = 0.f;
+      lsum[nb] += e;
+    }
+  }
+}
+
 template <typename T, int D, int MB>
 __global__ __launch_bounds__(512) void scores_pass1(ScoreArgs a) {
   using F = Frag<T>;
   using TL = Tile<T, D>;
   constexpr int kSteps = D / F::kElems;
-  __shared__ __attribute__((aligned(16))) char lds[TL::kBytes];
+  __shared__ __attribute__((aligned(1024))) char buf0[TL::kBytes];
+  __shared__ __attribute__((aligned(1024))) char buf1[TL::kBytes];
 
   const int chunk_id = blockIdx.x, slice = blockIdx.y;
   int l, b, g;
   slice_coords(a, slice, l, b, g);
   const int w = threadIdx.x >> 6, lane = threadIdx.x & 63, c32 = lane & 31, hh = lane >> 5;
-  const int s_w = MB * 32;
+  const int n_waves = blockDim.x >> 6;
+  constexpr int s_w = MB * 32;
   const T* q = reinterpret_cast<const T*>(a.q_win[l]) + b * a.qs[0] + (int64_t)(g * a.group + w) * a.qs[1];
-  const T* kbase = reinterpret_cast<const T*>(a.k[l]) + b * a.ks[0] + (int64_t)g * a.ks[1];
+  const char* kbase = reinterpret_cast<const char*>(reinterpret_cast<const T*>(a.k[l]) + b * a.ks[0] + (int64_t)g * a.ks[1]);
+  const int64_t tok_bytes = a.ks[2] * (int64_t)sizeof(T);
+
+  const int key0 = chunk_id * a.chunk;
+  const int key_end = min(key0 + a.chunk, a.n);
+  const int n_tiles = (key_end - key0 + kTileKeys - 1) / kTileKeys;
+  issue_tile<T, D>(buf0, kbase, tok_bytes, key0, a.n - 1, w, n_waves, lane);
 
   typename F::type qf[MB][kSteps];
-#pragma unroll
-  for (int nb = 0; nb < MB; ++nb)
-#pragma unroll
-    for (int s = 0; s < kSteps; ++s) qf[nb][s] = F::load(q + (int64_t)(nb * 32 + c32) * a.qs[2], s, hh);
-
+  load_q<T, D, MB>(qf, q, a.qs[2], c32, hh);
   float mref[MB], lsum[MB];
 #pragma unroll
   for (int nb = 0; nb < MB; ++nb) { mref[nb] = kMasked; lsum[nb] = 0.f; }
 
-  const int key0 = chunk_id * a.chunk;
-  const int key_end = min(key0 + a.chunk, a.n);
-  for (int t0 = key0; t0 < key_end; t0 += kTileKeys) {
-    __syncthreads();
-    stage_tile<T, D>(lds, kbase, a.ks[2], t0, a.n - 1);
-    __syncthreads();
+  auto stage = [&](const char* cur, char* nxt, int t) {
+    wait_vmem();
+    __syncthreads();                 // tile t complete in `cur`; everyone is done reading `nxt`
+    const int t0 = key0 + t * kTileKeys;
+    if (t + 1 < n_tiles) issue_tile<T, D>(nxt, kbase, tok_bytes, t0 + kTileKeys, a.n - 1, w, n_waves, lane);
 #pragma unroll
     for (int sub = 0; sub < kTileKeys / 32; ++sub) {
       const int kb = t0 + sub * 32;
       if (kb >= key_end) break;
-      f32x16 acc[MB];
-#pragma unroll
-      for (int nb = 0; nb < MB; ++nb)
-#pragma unroll
-        for (int v = 0; v < 16; ++v) acc[nb][v] = 0.f;
-      const char* krow = lds + (sub * 32 + c32) * TL::kPitch;
-#pragma unroll
-      for (int s = 0; s < kSteps; ++s) {
-        typename F::type kf = F::load(krow, s, hh);
-#pragma unroll
-        for (int nb = 0; nb < MB; ++nb) acc[nb] = F::mfma(kf, qf[nb][s], acc[nb]);
-      }
-      // acc[nb][v]: key = kb + 8*(v/4) + 4*hh + (v%4), window row = nb*32 + c32.
-      // Key j is visible to window row r iff j <= n_p + r (and j < n).
-      const bool tail = kb + 31 > a.n_p;   // some key of this sub-tile may be hidden or past the end
-#pragma unroll
-      for (int nb = 0; nb < MB; ++nb) {
-        float t[16];
-        const int last_visible = min(a.n_p + nb * 32 + c32, a.n - 1);
-        float tmax = kMasked;
-#pragma unroll
-        for (int v = 0; v < 16; ++v) {
-          t[v] = acc[nb][v] * a.c - mref[nb];
-          if (tail && kb + 8 * (v / 4) + 4 * hh + (v % 4) > last_visible) t[v] = kMasked;
-          tmax = fmaxf(tmax, t[v]);
-        }
-        const bool lift = tmax > kRescale;
-        if (__builtin_amdgcn_ballot_w64(lift)) {
-          if (lift) {
-            float rmax = kMasked;
-#pragma unroll
-            for (int v = 0; v < 16; ++v) {
-              bool hidden = tail && kb + 8 * (v / 4) + 4 * hh + (v % 4) > last_visible;
-              rmax = fmaxf(rmax, hidden ? kMasked : acc[nb][v] * a.c);
-            }
-            lsum[nb] *= exp2f(mref[nb] - rmax);
-            mref[nb] = rmax;
-#pragma unroll
-            for (int v = 0; v < 16; ++v) {
-              bool hidden = tail && kb + 8 * (v / 4) + 4 * hh + (v % 4) > last_visible;
-              t[v] = hidden ? kMasked : acc[nb][v] * a.c - rmax;
-            }
-          }
-        }
-#pragma unroll
-        for (int v = 0; v < 16; ++v) {
-          float e = exp2f(t[v]);
-          if (tail && kb + 8 * (v / 4) + 4 * hh + (v % 4) > last_visible) e = 0.f;
-          lsum[nb] += e;
-        }
-      }
+      if (kb + 31 > a.n_p)           // some key of this sub-tile may be hidden or past the end
+        pass1_subtile<T, D, MB, true>(cur, sub, kb, qf, mref, lsum, a.c, a.n, a.n_p, c32, hh);
+      else
+        pass1_subtile<T, D, MB, false>(cur, sub, kb, qf, mref, lsum, a.c, a.n, a.n_p, c32, hh);
     }
+  };
+  for (int t = 0; t < n_tiles; t += 2) {
+    stage(buf0, buf1, t);
+    if (t + 1 < n_tiles) stage(buf1, buf0, t + 1);
   }
+
   // Merge the two lane halves of each window row and store the chunk's pair.
   float* out = a.part + (((int64_t)slice * a.n_chunks + chunk_id) * (a.group * s_w) + w * s_w) * 2;
 #pragma unroll
   for (int nb = 0; nb < MB; ++nb) {
     float om = __shfl_xor(mref[nb], 32), ol = __shfl_xor(lsum[nb], 32);
     float m = fmaxf(mref[nb], om);
-    float s = lsum[nb] * exp2f(mref[nb] - m) + ol * exp2f(om - m);
+    float s = lsum[nb] * fast_exp2(mref[nb] - m) + ol * fast_exp2(om - m);
     if (hh == 0) {
       out[(nb * 32 + c32) * 2 + 0] = m;
       out[(nb * 32 + c32) * 2 + 1] = s;
@@ -227,28 +280,74 @@ __global__ void scores_combine(ScoreArgs a, int rows_per_slice, int64_t total_ro
 // Pass 2: normalised weights on the prefix columns; column Mean/Var, entropy, group mean.
 // ------------------------------------------------------------------------------------------
 template <typename T, int D, int MB>
+__device__ __forceinline__ void pass2_subtile(const char* tile, int sub, int kb, int key_end,
+                                              const typename Frag<T>::type (&qf)[MB][D / Frag<T>::kElems],
+                                              const float (&lse_r)[MB][16], const ScoreArgs& a, float& ent_acc,
+                                              float& var_acc, float* iq_row, int c32, int hh) {
+  using F = Frag<T>;
+  using TL = Tile<T, D>;
+  constexpr int kSteps = D / F::kElems;
+  f32x16 acc[MB];
+#pragma unroll
+  for (int mb = 0; mb < MB; ++mb)
+#pragma unroll
+    for (int v = 0; v < 16; ++v) acc[mb][v] = 0.f;
+#pragma unroll
+  for (int s = 0; s < kSteps; ++s) {
+    typename F::type kf = F::template load_lds<TL>(tile, sub * 32 + c32, s, hh);
+#pragma unroll
+    for (int mb = 0; mb < MB; ++mb) acc[mb] = F::mfma(qf[mb][s], kf, acc[mb]);
+  }
+  // acc[mb][v]: window row mb*32 + 8*(v/4) + 4*hh + (v%4) of key column kb + c32.
+  float sp = 0.f, sp2 = 0.f, ent = 0.f;
+#pragma unroll
+  for (int mb = 0; mb < MB; ++mb)
+#pragma unroll
+    for (int v = 0; v < 16; ++v) {
+      const float t = acc[mb][v] * a.c - lse_r[mb][v];   // log2 of the attention weight
+      const float p = fast_exp2(t);
+      sp += p;
+      sp2 = fmaf(p, p, sp2);
+      ent = fmaf(p, t, ent);
+    }
+  sp += __shfl_xor(sp, 32);
+  sp2 += __shfl_xor(sp2, 32);
+  const bool valid = kb + c32 < key_end;
+  const float mean = sp * a.inv_sw;
+  const float var = fmaxf((sp2 - sp * mean) * a.inv_swc, 0.f);
+  if (valid) {
+    ent_acc += ent;
+    if (hh == 0) var_acc += var;
+  }
+  if (hh == 0) iq_row[sub * 32 + c32] = valid ? mean + a.gamma * var : 0.f;
+}
+
+template <typename T, int D, int MB>
 __global__ __launch_bounds__(512) void scores_pass2(ScoreArgs a) {
   using F = Frag<T>;
   using TL = Tile<T, D>;
   constexpr int kSteps = D / F::kElems;
-  __shared__ __attribute__((aligned(16))) char lds[TL::kBytes];
-  __shared__ float iq_lds[8][kTileKeys];
+  __shared__ __attribute__((aligned(1024))) char buf0[TL::kBytes];
+  __shared__ __attribute__((aligned(1024))) char buf1[TL::kBytes];
+  __shared__ float iq_lds[2][8][kTileKeys];
 
   const int chunk_id = blockIdx.x, slice = blockIdx.y;
   int l, b, g;
   slice_coords(a, slice, l, b, g);
   const int w = threadIdx.x >> 6, lane = threadIdx.x & 63, c32 = lane & 31, hh = lane >> 5;
-  const int s_w = MB * 32;
+  const int n_waves = blockDim.x >> 6;
+  constexpr int s_w = MB * 32;
   const T* q = reinterpret_cast<const T*>(a.q_win[l]) + b * a.qs[0] + (int64_t)(g * a.group + w) * a.qs[1];
-  const T* kbase = reinterpret_cast<const T*>(a.k[l]) + b * a.ks[0] + (int64_t)g * a.ks[1];
+  const char* kbase = reinterpret_cast<const char*>(reinterpret_cast<const T*>(a.k[l]) + b * a.ks[0] + (int64_t)g * a.ks[1]);
+  const int64_t tok_bytes = a.ks[2] * (int64_t)sizeof(T);
+
+  const int key0 = chunk_id * a.chunk;
+  const int key_end = min(key0 + a.chunk, a.n_p);
+  const int n_tiles = (key_end - key0 + kTileKeys - 1) / kTileKeys;
+  issue_tile<T, D>(buf0, kbase, tok_bytes, key0, a.n - 1, w, n_waves, lane);
 
   typename F::type qf[MB][kSteps];
-#pragma unroll
-  for (int mb = 0; mb < MB; ++mb)
-#pragma unroll
-    for (int s = 0; s < kSteps; ++s) qf[mb][s] = F::load(q + (int64_t)(mb * 32 + c32) * a.qs[2], s, hh);
-
-  // acc[mb][v] will hold window row mb*32 + 8*(v/4) + 4*hh + (v%4) of key column c32.
+  load_q<T, D, MB>(qf, q, a.qs[2], c32, hh);
   float lse_r[MB][16];
   const float* lse = a.lse + (int64_t)slice * (a.group * s_w) + w * s_w;
 #pragma unroll
@@ -257,61 +356,40 @@ __global__ __launch_bounds__(512) void scores_pass2(ScoreArgs a) {
     for (int v = 0; v < 16; ++v) lse_r[mb][v] = lse[mb * 32 + 8 * (v / 4) + 4 * hh + (v % 4)];
 
   float ent_acc = 0.f, var_acc = 0.f;
-  const int key0 = chunk_id * a.chunk;
-  const int key_end = min(key0 + a.chunk, a.n_p);
   float* raw = a.raw + (int64_t)slice * a.n_p;
-  for (int t0 = key0; t0 < key_end; t0 += kTileKeys) {
-    __syncthreads();
-    stage_tile<T, D>(lds, kbase, a.ks[2], t0, a.n - 1);
-    __syncthreads();
+
+  // Group mean of the G heads' I_q for the 64 keys of tile t, written by the first wave.
+  auto flush = [&](int t) {
+    const int key = key0 + t * kTileKeys + (int)threadIdx.x;
+    if (threadIdx.x < kTileKeys && key < key_end) {
+      float s = 0.f;
+      for (int ww = 0; ww < a.group; ++ww) s += iq_lds[t & 1][ww][threadIdx.x];
+      raw[key] = s * a.inv_g;
+    }
+  };
+  auto stage = [&](const char* cur, char* nxt, int t) {
+    wait_vmem();
+    __syncthreads();       // tile t complete in `cur`; `nxt` and iq_lds[t&1] free; tile t-1's I_q written
+    const int t0 = key0 + t * kTileKeys;
+    if (t + 1 < n_tiles) issue_tile<T, D>(nxt, kbase, tok_bytes, t0 + kTileKeys, a.n - 1, w, n_waves, lane);
+    if (t > 0) flush(t - 1);
 #pragma unroll
     for (int sub = 0; sub < kTileKeys / 32; ++sub) {
       const int kb = t0 + sub * 32;
-      if (kb >= key_end) {           // whole sub-tile beyond the prefix: contributes zeros
-        if (hh == 0) iq_lds[w][sub * 32 + c32] = 0.f;
+      if (kb >= key_end) {           // whole sub-tile beyond the prefix
+        if (hh == 0) iq_lds[t & 1][w][sub * 32 + c32] = 0.f;
         continue;
       }
-      f32x16 acc[MB];
-#pragma unroll
-      for (int mb = 0; mb < MB; ++mb)
-#pragma unroll
-        for (int v = 0; v < 16; ++v) acc[mb][v] = 0.f;
-      const char* krow = lds + (sub * 32 + c32) * TL::kPitch;
-#pragma unroll
-      for (int s = 0; s < kSteps; ++s) {
-        typename F::type kf = F::load(krow, s, hh);
-#pragma unroll
-        for (int mb = 0; mb < MB; ++mb) acc[mb] = F::mfma(qf[mb][s], kf, acc[mb]);
-      }
-      float sp = 0.f, sp2 = 0.f, ent = 0.f;
-#pragma unroll
-      for (int mb = 0; mb < MB; ++mb)
-#pragma unroll
-        for (int v = 0; v < 16; ++v) {
-          float t = acc[mb][v] * a.c - lse_r[mb][v];   // log2 of the attention weight
-          float p = exp2f(t);
-          sp += p;
-          sp2 = fmaf(p, p, sp2);
-          ent = fmaf(p, t, ent);
-        }
-      sp += __shfl_xor(sp, 32);
-      sp2 += __shfl_xor(sp2, 32);
-      const bool valid = kb + c32 < key_end;
-      const float mean = sp * a.inv_sw;
-      const float var = fmaxf((sp2 - sp * mean) * a.inv_swc, 0.f);
-      if (valid) {
-        ent_acc += ent;
-        if (hh == 0) var_acc += var;
-      }
-      if (hh == 0) iq_lds[w][sub * 32 + c32] = valid ? mean + a.gamma * var : 0.f;
+      pass2_subtile<T, D, MB>(cur, sub, kb, key_end, qf, lse_r, a, ent_acc, var_acc, iq_lds[t & 1][w], c32, hh);
     }
-    __syncthreads();
-    if (threadIdx.x < kTileKeys && t0 + (int)threadIdx.x < key_end) {
-      float s = 0.f;
-      for (int ww = 0; ww < a.group; ++ww) s += iq_lds[ww][threadIdx.x];
-      raw[t0 + threadIdx.x] = s * a.inv_g;
-    }
+  };
+  for (int t = 0; t < n_tiles; t += 2) {
+    stage(buf0, buf1, t);
+    if (t + 1 < n_tiles) stage(buf1, buf0, t + 1);
   }
+  __syncthreads();
+  flush(n_tiles - 1);
+
   // Per-wave sums in a fixed order.
 #pragma unroll
   for (int off = 32; off >= 1; off >>= 1) {
