@@ -32,6 +32,8 @@ def parse_args():
     ap.add_argument("--config", type=int, default=4, help="synthetic config id (4 = 128K context, the headline)")
     ap.add_argument("--layers", type=int, default=0, help="override layer count (0 = the config's)")
     ap.add_argument("--no-cpu-baseline", action="store_true", help="skip the oracle timing (profiling runs)")
+    ap.add_argument("--copy-calibration", action="store_true",
+                    help="also run a plain 1 GiB device copy four times (reference for the HBM byte counters)")
     return ap.parse_args()
 
 
@@ -76,6 +78,18 @@ def cpu_baseline(cfg, layer_inputs, params):
                       f"scaled by the fraction of a layer done"}
 
 
+def measured_traffic(cfg, kernel):
+    """HBM bytes per launch of `kernel` from the committed rocprofv3 counter runs (FETCH_SIZE +
+    WRITE_SIZE, scaled by what the same counters read for a plain copy), or None if not measured
+    for this workload."""
+    path = os.path.join(ROOT, "profiles", "hbm_traffic.json")
+    try:
+        table = json.load(open(path))
+        return table[f"config{cfg.cid}"]["kernels"][kernel]["hbm_bytes"]
+    except Exception:
+        return None
+
+
 def main():
     args = parse_args()
     if args.gpus != 1:
@@ -113,6 +127,14 @@ def main():
     params = cake.make_params()
     ev = cake.EvictionPass([q_all[l] for l in range(L)], [k_all[l] for l in range(L)], [v_all[l] for l in range(L)],
                            cfg.total_budget, params)
+
+    if args.copy_calibration:
+        src = torch.empty(1 << 30, dtype=torch.uint8, device=dev).fill_(1)
+        dst = torch.empty_like(src)
+        for _ in range(4):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
 
     for _ in range(args.warmup):
         ev.run()
@@ -176,7 +198,7 @@ def main():
     flops_pass = 2.0 * tokens_layers * cfg.n_q_heads * cfg.window * cfg.head_dim   # one logits pass
     achieved = alg[dominant] / dom_s / 1e9
     roofline = {"kernel": dominant, "bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBPS, "unit": "GB/s",
-                "frac": achieved / HBM_PEAK_GBPS, "traffic": None}
+                "frac": achieved / HBM_PEAK_GBPS, "traffic": measured_traffic(cfg, dominant)}
     mfma_peak = MFMA_BF16_PEAK_TFLOPS if cfg.dtype == "bf16" else MFMA_F32_PEAK_TFLOPS
     extra = {
         "kernel_ms": {n: round(v, 4) for n, v in kernel_ms.items()},
