@@ -56,10 +56,9 @@ ScoreLayout score_layout(const cake_shape& s) {
   const int64_t n_p = (int64_t)s.seq_len - s.window;
   w.n_slices = (int64_t)s.n_layers * s.batch * s.n_kv_heads;
   w.rows = g * s.window;
-  // Chunks of up to 2048 keys; shrink (down to 256) while the pass would launch fewer than
-  // 2048 workgroups, eight per compute unit.
-  int chunk = 2048;
-  while (chunk > 256 && w.n_slices * ((s.seq_len + chunk - 1) / chunk) < 2048) chunk /= 2;
+  // The chunk depends on N alone, so that a layer's sums are grouped the same way (and come out
+  // bit-identical) whether it is scored alone (cascading) or batched with other layers.
+  const int chunk = s.seq_len >= 32768 ? 2048 : s.seq_len >= 8192 ? 1024 : s.seq_len >= 2048 ? 512 : 256;
   w.chunk = chunk;
   w.n_chunks = (s.seq_len + chunk - 1) / chunk;
   w.n_chunks_p = (int32_t)((n_p + chunk - 1) / chunk);

@@ -144,3 +144,76 @@ class EvictionPass:
         keep, idx, k_out, v_out, ind_out = self.evict(budgets)
         return PassResult(budgets, keep, pref, hv, [self.indicator[l] for l in range(self.L)], idx, k_out, v_out,
                           ind_out)
+
+    def run_cascade(self, track_positions: bool = True) -> PassResult:
+        """Cascading pass (Sec. 4.2, Alg. 1).  Stage m scores layer m, recomputes B^(m) over the
+        layers seen so far (Eq. 9) and applies EVICT to each of them on its current, already
+        compacted cache and indicator, all affected layers batched into one top-k and one
+        compaction call.  A layer whose budget did not shrink is left as it is (EVICT would keep
+        everything).  With `track_positions` the retained rows' original prefix positions are
+        carried along (index bookkeeping with torch.gather, not part of the method).
+        """
+        L, B, S_w, N_p = self.L, self.B, self.S_w, self.N_p
+        shape1 = C.make_shape(B, 1, self.H_q, self.H_kv, self.d, self.N, S_w, self.dtype)
+        ws1 = torch.empty(C.cake_workspace_bytes(shape1), dtype=torch.uint8, device=self.dev)
+        pref1 = torch.empty(B, 1, dtype=torch.float64, device=self.dev)
+        hv1 = torch.empty(B, 1, 2, dtype=torch.float64, device=self.dev)
+        pref = np.zeros((B, L))
+        hv = np.zeros((B, L, 2))
+        cur_k: List[torch.Tensor] = [None] * L       # current caches [B,H_kv,cap+S_w,d]
+        cur_v: List[torch.Tensor] = [None] * L
+        cur_i: List[torch.Tensor] = [None] * L       # current indicators [B,H_kv,cap]
+        cur_pos: List[Optional[torch.Tensor]] = [None] * L
+        cur_len = np.zeros((L, B), dtype=np.int64)
+        stage_budgets = []
+        budgets = None
+        for m in range(L):
+            # ---- admit layer m: indicator and preference
+            C.cake_window_scores(shape1, self.params, self.tbl_q[m:m + 1], self.tbl_k[m:m + 1],
+                                 _strides3(self.q_win[m]), _strides3(self.k[m]), self.tbl_ind[m:m + 1], ws1)
+            C.cake_layer_preference(shape1, self.params, ws1, pref1, hv1)
+            pref[:, m] = pref1.cpu().numpy()[:, 0]
+            hv[:, m] = hv1.cpu().numpy()[:, 0]
+            cur_k[m], cur_v[m], cur_i[m] = self.k[m], self.v[m], self.indicator[m]
+            cur_len[m, :] = N_p
+            if track_positions:
+                cur_pos[m] = torch.arange(N_p, device=self.dev, dtype=torch.int64).expand(B, self.H_kv, N_p)
+            # ---- B^(m) for the layers seen so far
+            budgets = np.empty((m + 1, B), dtype=np.int64)
+            for b in range(B):
+                budgets[:, b] = C.cake_cascade_allocate(pref[b, : m + 1], self.total_budget, S_w, self.N)
+            stage_budgets.append(budgets.copy())
+            keep = np.minimum(np.maximum(budgets - S_w, 0), cur_len[: m + 1])
+            layers = [l for l in range(m + 1) if np.any(keep[l] < cur_len[l])]
+            if not layers:
+                continue
+            # ---- EVICT the affected layers in one batched call each
+            n = len(layers)
+            shape_n = C.make_shape(B, n, self.H_q, self.H_kv, self.d, self.N, S_w, self.dtype)
+            caps = [int(keep[l].max()) for l in layers]
+            # zero-filled: with a ragged batch the entries past a sequence's own count are never
+            # written by the library, and the position bookkeeping below gathers through them
+            idx = [torch.zeros(B, self.H_kv, max(c, 1), dtype=torch.int32, device=self.dev) for c in caps]
+            k_out = [torch.empty(B, self.H_kv, c + S_w, self.d, dtype=self.dtype, device=self.dev) for c in caps]
+            v_out = [torch.empty_like(t) for t in k_out]
+            i_out = [torch.empty(B, self.H_kv, max(c, 1), dtype=torch.float32, device=self.dev) for c in caps]
+            cl = [int(x) for l in layers for x in cur_len[l]]
+            kk = [int(x) for l in layers for x in keep[l]]
+            t_idx = C.ptr_table(idx)
+            C.cake_select_topk(shape_n, C.ptr_table([cur_i[l] for l in layers]), cl, kk, t_idx)
+            C.cake_compact_kv(shape_n, C.ptr_table([cur_k[l] for l in layers]), C.ptr_table([cur_v[l] for l in layers]),
+                              [_strides3(cur_k[l]) for l in layers], cl, kk, t_idx,
+                              C.ptr_table([cur_i[l] for l in layers]), C.ptr_table(k_out), C.ptr_table(v_out),
+                              C.ptr_table(i_out))
+            for j, l in enumerate(layers):
+                if track_positions:
+                    c = caps[j]
+                    cur_pos[l] = torch.gather(cur_pos[l], 2, idx[j][:, :, :c].long()) if c else cur_pos[l][:, :, :0]
+                cur_k[l], cur_v[l], cur_i[l] = k_out[j], v_out[j], i_out[j]
+                cur_len[l] = keep[l]
+        torch.cuda.synchronize()
+        keep_final = cur_len.copy()
+        idx_final = [p.to(torch.int32) if p is not None else None for p in cur_pos]
+        return PassResult(budgets, keep_final, pref, hv, [self.indicator[l] for l in range(L)], idx_final, cur_k, cur_v,
+                          cur_i, stage_budgets)
+
