@@ -38,7 +38,6 @@ typedef __attribute__((address_space(3))) void* lds_ptr;
 
 constexpr int kTileKeys = 64;        // keys staged per LDS tile (two 32-key MFMA sub-tiles)
 constexpr float kMasked = -1.0e30f;  // stands for -inf without producing NaN in differences
-constexpr float kRescale = 40.0f;    // pass 1 re-references a row when a logit exceeds it by 2^40
 
 __device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }  // v_exp_f32
 
@@ -161,15 +160,23 @@ __device__ __forceinline__ void pass1_subtile(const char* tile, int sub, int kb,
 #pragma unroll
   for (int nb = 0; nb < MB; ++nb) {
     const int last_visible = min(n_p + nb * 32 + c32, n - 1);
-    float t[16];
-    float tmax = kMasked;
+    float part[4] = {0.f, 0.f, 0.f, 0.f};     // independent partial sums of the block's 16 terms
 #pragma unroll
-    for (int v = 0; v < 16; ++v) {
-      t[v] = acc[nb][v] * c - mref[nb];
-      if (kTail && kb + 8 * (v / 4) + 4 * hh + (v % 4) > last_visible) t[v] = kMasked;
-      tmax = fmaxf(tmax, t[v]);
+    for (int v4 = 0; v4 < 16; v4 += 4) {
+      float e[4];
+#pragma unroll
+      for (int i = 0; i < 4; ++i) e[i] = fast_exp2(acc[nb][v4 + i] * c - mref[nb]);
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+        const int v = v4 + i;
+        if (kTail && kb + 8 * (v / 4) + 4 * hh + (v % 4) > last_visible) e[i] = 0.f;
+        part[i] += e[i];
+      }
     }
-    const bool lift = tmax > kRescale;
+    float block = (part[0] + part[1]) + (part[2] + part[3]);
+    // Sixteen terms of at most 2^40 each add at most 2^44.  Anything above that (or inf/NaN)
+    // means a logit outran the row's reference: redo the block with a reference of its own.
+    const bool lift = !(block <= 16.f * 1.0995116e12f);
     if (__builtin_amdgcn_ballot_w64(lift)) {
       if (lift) {
         float rmax = kMasked;
@@ -180,19 +187,15 @@ __device__ __forceinline__ void pass1_subtile(const char* tile, int sub, int kb,
         }
         lsum[nb] *= fast_exp2(mref[nb] - rmax);
         mref[nb] = rmax;
+        block = 0.f;
 #pragma unroll
         for (int v = 0; v < 16; ++v) {
           const bool hidden = kTail && kb + 8 * (v / 4) + 4 * hh + (v % 4) > last_visible;
-          t[v] = hidden ? kMasked : acc[nb][v] * c - rmax;
+          block += hidden ? 0.f : fast_exp2(acc[nb][v] * c - rmax);
         }
       }
     }
-#pragma unroll
-    for (int v = 0; v < 16; ++v) {
-      float e = fast_exp2(t[v]);
-      if (kTail && kb + 8 * (v / 4) + 4 * hh + (v % 4) > last_visible) e = 0.f;
-      lsum[nb] += e;
-    }
+    lsum[nb] += block;
   }
 }
 
@@ -279,6 +282,12 @@ __global__ void scores_combine(ScoreArgs a, int rows_per_slice, int64_t total_ro
 // ------------------------------------------------------------------------------------------
 // Pass 2: normalised weights on the prefix columns; column Mean/Var, entropy, group mean.
 // ------------------------------------------------------------------------------------------
+// Sum of x over the two lane halves, delivered to both.
+__device__ __forceinline__ float add_halves(float x) {
+  auto r = __builtin_amdgcn_permlane32_swap(__float_as_uint(x), __float_as_uint(x), false, false);
+  return __uint_as_float(r[0]) + __uint_as_float(r[1]);
+}
+
 template <typename T, int D, int MB>
 __device__ __forceinline__ void pass2_subtile(const char* tile, int sub, int kb, int key_end,
                                               const typename Frag<T>::type (&qf)[MB][D / Frag<T>::kElems],
@@ -299,19 +308,27 @@ __device__ __forceinline__ void pass2_subtile(const char* tile, int sub, int kb,
     for (int mb = 0; mb < MB; ++mb) acc[mb] = F::mfma(qf[mb][s], kf, acc[mb]);
   }
   // acc[mb][v]: window row mb*32 + 8*(v/4) + 4*hh + (v%4) of key column kb + c32.
-  float sp = 0.f, sp2 = 0.f, ent = 0.f;
+  // Four independent accumulator sets: consecutive logits do not wait on each other's adds.
+  float spv[4] = {0.f, 0.f, 0.f, 0.f}, sp2v[4] = {0.f, 0.f, 0.f, 0.f}, entv[4] = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
   for (int mb = 0; mb < MB; ++mb)
 #pragma unroll
-    for (int v = 0; v < 16; ++v) {
-      const float t = acc[mb][v] * a.c - lse_r[mb][v];   // log2 of the attention weight
-      const float p = fast_exp2(t);
-      sp += p;
-      sp2 = fmaf(p, p, sp2);
-      ent = fmaf(p, t, ent);
+    for (int v4 = 0; v4 < 16; v4 += 4) {
+      float t[4], p[4];
+#pragma unroll
+      for (int i = 0; i < 4; ++i) t[i] = acc[mb][v4 + i] * a.c - lse_r[mb][v4 + i];   // log2 of the weight
+#pragma unroll
+      for (int i = 0; i < 4; ++i) p[i] = fast_exp2(t[i]);
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+        spv[i] += p[i];
+        sp2v[i] = fmaf(p[i], p[i], sp2v[i]);
+        entv[i] = fmaf(p[i], t[i], entv[i]);
+      }
     }
-  sp += __shfl_xor(sp, 32);
-  sp2 += __shfl_xor(sp2, 32);
+  const float ent = (entv[0] + entv[1]) + (entv[2] + entv[3]);
+  const float sp = add_halves((spv[0] + spv[1]) + (spv[2] + spv[3]));
+  const float sp2 = add_halves((sp2v[0] + sp2v[1]) + (sp2v[2] + sp2v[3]));
   const bool valid = kb + c32 < key_end;
   const float mean = sp * a.inv_sw;
   const float var = fmaxf((sp2 - sp * mean) * a.inv_swc, 0.f);
