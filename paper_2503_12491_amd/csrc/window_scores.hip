@@ -97,22 +97,54 @@ struct ScoreArgs {
   float* raw;                // [slice][n_p]
 };
 
-// Start the transfer of keys [t0, t0+64) of one slice into an LDS tile.  Each wave issues
-// whole 1 KiB groups; lane i of a group fills LDS bytes [16 i, 16 i + 16) of that group and
-// fetches the piece of the key row that the swizzle assigns to that place.  Rows past the last
-// key are clamped to it (their logits are masked later), so every access stays inside the slice.
+// Transfer of keys [t0, t0+64) of one slice into an LDS tile.  The tile is moved as 1 KiB
+// groups, one wave-wide instruction each, group i by wave i mod G.  Lane j of a group fills LDS
+// bytes [16 j, 16 j + 16) of that group and fetches the piece of the key row that the swizzle
+// assigns to that place.  The per-lane part of the source offset takes only kVariants distinct
+// values (the swizzle repeats every kPieces rows), which are computed once per kernel; per
+// transfer there remain a scalar base and one select.  Rows past the last key are clamped to it
+// (their logits are masked later), so every access stays inside the slice.
 template <typename T, int D>
-__device__ __forceinline__ void issue_tile(char* tile, const char* kbase, int64_t tok_bytes, int t0, int last_key,
-                                           int wave, int n_waves, int lane) {
+struct TileMover {
   using TL = Tile<T, D>;
-  for (int i = wave; i < TL::kGroups; i += n_waves) {
-    const int off = i * 1024 + lane * 16;
-    const int r = off / TL::kRowBytes, slot = (off % TL::kRowBytes) >> 4;
-    const int q = slot ^ (r & (TL::kPieces - 1));
-    const char* src = kbase + (int64_t)min(t0 + r, last_key) * tok_bytes + q * 16;
-    __builtin_amdgcn_global_load_lds((global_cptr)src, (lds_ptr)(tile + i * 1024), 16, 0, 0);
+  static constexpr int kRows = 1024 / TL::kRowBytes;                           // key rows per group
+  static constexpr int kVariants = TL::kPieces > kRows ? TL::kPieces / kRows : 1;
+  static constexpr bool kFast = kVariants <= 4;
+  uint32_t off0, off1, off2, off3;          // per-lane source offsets of the (at most four) variants
+  const char* kbase;
+  int64_t tok_bytes;
+  int last_key, wave, n_waves, lane;
+
+  __device__ __forceinline__ void init(const char* kbase_, int64_t tok_bytes_, int last_key_, int wave_, int n_waves_,
+                                       int lane_) {
+    kbase = kbase_; tok_bytes = tok_bytes_; last_key = last_key_; wave = wave_; n_waves = n_waves_; lane = lane_;
+    const int lr = lane / TL::kPieces, slot = lane % TL::kPieces;
+    auto variant = [&](int m) {
+      const int q = slot ^ ((m * kRows + lr) & (TL::kPieces - 1));
+      return (uint32_t)(lr * tok_bytes + q * 16);
+    };
+    off0 = variant(0); off1 = variant(1 % kVariants); off2 = variant(2 % kVariants); off3 = variant(3 % kVariants);
   }
-}
+  __device__ __forceinline__ void issue(char* tile, int t0) const {
+    if (kFast && t0 + kTileKeys - 1 <= last_key) {       // whole tile inside the slice
+      const char* base = kbase + (int64_t)t0 * tok_bytes;
+      for (int i = wave; i < TL::kGroups; i += n_waves) {
+        const int m = i % kVariants;
+        const uint32_t off = m == 0 ? off0 : m == 1 ? off1 : m == 2 ? off2 : off3;
+        const char* src = base + (int64_t)i * kRows * tok_bytes + off;
+        __builtin_amdgcn_global_load_lds((global_cptr)src, (lds_ptr)(tile + i * 1024), 16, 0, 0);
+      }
+    } else {
+      for (int i = wave; i < TL::kGroups; i += n_waves) {
+        const int off = i * 1024 + lane * 16;
+        const int r = off / TL::kRowBytes, slot = (off % TL::kRowBytes) >> 4;
+        const int q = slot ^ (r & (TL::kPieces - 1));
+        const char* src = kbase + (int64_t)min(t0 + r, last_key) * tok_bytes + q * 16;
+        __builtin_amdgcn_global_load_lds((global_cptr)src, (lds_ptr)(tile + i * 1024), 16, 0, 0);
+      }
+    }
+  }
+};
 
 // All of this wave's outstanding vector-memory operations (the tile transfers) have landed.
 __device__ __forceinline__ void wait_vmem() { __builtin_amdgcn_s_waitcnt(0x0F70); }   // vmcnt(0)
@@ -210,7 +242,8 @@ __global__ __launch_bounds__(512) void scores_pass1(ScoreArgs a) {
   const int chunk_id = blockIdx.x, slice = blockIdx.y;
   int l, b, g;
   slice_coords(a, slice, l, b, g);
-  const int w = threadIdx.x >> 6, lane = threadIdx.x & 63, c32 = lane & 31, hh = lane >> 5;
+  const int w = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);   // wave index, known uniform
+  const int lane = threadIdx.x & 63, c32 = lane & 31, hh = lane >> 5;
   const int n_waves = blockDim.x >> 6;
   constexpr int s_w = MB * 32;
   const T* q = reinterpret_cast<const T*>(a.q_win[l]) + b * a.qs[0] + (int64_t)(g * a.group + w) * a.qs[1];
@@ -220,7 +253,9 @@ __global__ __launch_bounds__(512) void scores_pass1(ScoreArgs a) {
   const int key0 = chunk_id * a.chunk;
   const int key_end = min(key0 + a.chunk, a.n);
   const int n_tiles = (key_end - key0 + kTileKeys - 1) / kTileKeys;
-  issue_tile<T, D>(buf0, kbase, tok_bytes, key0, a.n - 1, w, n_waves, lane);
+  TileMover<T, D> mover;
+  mover.init(kbase, tok_bytes, a.n - 1, w, n_waves, lane);
+  mover.issue(buf0, key0);
 
   typename F::type qf[MB][kSteps];
   load_q<T, D, MB>(qf, q, a.qs[2], c32, hh);
@@ -232,7 +267,7 @@ __global__ __launch_bounds__(512) void scores_pass1(ScoreArgs a) {
     wait_vmem();
     __syncthreads();                 // tile t complete in `cur`; everyone is done reading `nxt`
     const int t0 = key0 + t * kTileKeys;
-    if (t + 1 < n_tiles) issue_tile<T, D>(nxt, kbase, tok_bytes, t0 + kTileKeys, a.n - 1, w, n_waves, lane);
+    if (t + 1 < n_tiles) mover.issue(nxt, t0 + kTileKeys);
 #pragma unroll
     for (int sub = 0; sub < kTileKeys / 32; ++sub) {
       const int kb = t0 + sub * 32;
@@ -351,7 +386,8 @@ __global__ __launch_bounds__(512) void scores_pass2(ScoreArgs a) {
   const int chunk_id = blockIdx.x, slice = blockIdx.y;
   int l, b, g;
   slice_coords(a, slice, l, b, g);
-  const int w = threadIdx.x >> 6, lane = threadIdx.x & 63, c32 = lane & 31, hh = lane >> 5;
+  const int w = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);   // wave index, known uniform
+  const int lane = threadIdx.x & 63, c32 = lane & 31, hh = lane >> 5;
   const int n_waves = blockDim.x >> 6;
   constexpr int s_w = MB * 32;
   const T* q = reinterpret_cast<const T*>(a.q_win[l]) + b * a.qs[0] + (int64_t)(g * a.group + w) * a.qs[1];
@@ -361,7 +397,9 @@ __global__ __launch_bounds__(512) void scores_pass2(ScoreArgs a) {
   const int key0 = chunk_id * a.chunk;
   const int key_end = min(key0 + a.chunk, a.n_p);
   const int n_tiles = (key_end - key0 + kTileKeys - 1) / kTileKeys;
-  issue_tile<T, D>(buf0, kbase, tok_bytes, key0, a.n - 1, w, n_waves, lane);
+  TileMover<T, D> mover;
+  mover.init(kbase, tok_bytes, a.n - 1, w, n_waves, lane);
+  mover.issue(buf0, key0);
 
   typename F::type qf[MB][kSteps];
   load_q<T, D, MB>(qf, q, a.qs[2], c32, hh);
@@ -388,7 +426,7 @@ __global__ __launch_bounds__(512) void scores_pass2(ScoreArgs a) {
     wait_vmem();
     __syncthreads();       // tile t complete in `cur`; `nxt` and iq_lds[t&1] free; tile t-1's I_q written
     const int t0 = key0 + t * kTileKeys;
-    if (t + 1 < n_tiles) issue_tile<T, D>(nxt, kbase, tok_bytes, t0 + kTileKeys, a.n - 1, w, n_waves, lane);
+    if (t + 1 < n_tiles) mover.issue(nxt, t0 + kTileKeys);
     if (t > 0) flush(t - 1);
 #pragma unroll
     for (int sub = 0; sub < kTileKeys / 32; ++sub) {
@@ -541,6 +579,7 @@ extern "C" int cake_window_scores(const cake_shape* shape, const cake_params* pa
     CAKE_REQUIRE((q_strides[i] * eb) % 16 == 0 && (k_strides[i] * eb) % 16 == 0, "strides must be multiples of 16 bytes");
   }
   CAKE_REQUIRE(q_strides[2] >= shape->head_dim && k_strides[2] >= shape->head_dim, "token stride below head_dim");
+  CAKE_REQUIRE(k_strides[2] * (int64_t)eb <= (int64_t)1 << 27, "key token stride above 128 MiB");
   const ScoreLayout lay = score_layout(*shape);
   if (workspace == nullptr || (reinterpret_cast<uintptr_t>(workspace) & 255) != 0)
     return fail(CAKE_ERR_WORKSPACE, "workspace is NULL or not 256-byte aligned");
