@@ -148,9 +148,10 @@ def main():
     e = [[torch.cuda.Event(enable_timing=True) for _ in range(5)] for _ in range(args.steps)]
     torch.cuda.synchronize()
     t_start = time.perf_counter()
+    q_str = [q_all[0].stride(i) for i in range(3)]
+    k_str = [k_all[0].stride(i) for i in range(3)]
     for s in range(args.steps):
-        cake.cake_window_scores(ev.shape, ev.params, ev.tbl_q, ev.tbl_k, [q_all[0].stride(i) for i in range(3)],
-                                [k_all[0].stride(i) for i in range(3)], ev.tbl_ind, ev.workspace)
+        cake.cake_window_scores(ev.shape, ev.params, ev.tbl_q, ev.tbl_k, q_str, k_str, ev.tbl_ind, ev.workspace)
         e[s][0].record()
         cake.cake_layer_preference(ev.shape, ev.params, ev.workspace, ev.pref, ev.hv)
         e[s][1].record()
@@ -158,14 +159,12 @@ def main():
         ms4 = cake.cake_profile_read()           # events already complete: the stream was just synchronised
         budgets = ev.allocate(pref)
         keep = np.minimum(np.maximum(budgets - ev.S_w, 0), ev.N_p)
-        idx, k_out, v_out, ind_out = ev._carve_outputs(keep)
-        cur = [ev.N_p] * (L * B)
-        kk = [int(x) for x in keep.reshape(-1)]
+        ev._carve_outputs(keep)
+        kk = keep.reshape(-1).tolist()
         e[s][2].record()
-        cake.cake_select_topk(ev.shape, ev.tbl_ind, cur, kk, ev.tbl_out[0])
+        cake.cake_select_topk(ev.shape, ev.tbl_ind, ev._cur_full, kk, ev.tbl_out[0])
         e[s][3].record()
-        strides = [[k_all[0].stride(i) for i in range(3)]] * L
-        cake.cake_compact_kv(ev.shape, ev.tbl_k, ev.tbl_v, strides, cur, kk, ev.tbl_out[0], ev.tbl_ind,
+        cake.cake_compact_kv(ev.shape, ev.tbl_k, ev.tbl_v, ev._strides_full, ev._cur_full, kk, ev.tbl_out[0], ev.tbl_ind,
                              ev.tbl_out[1], ev.tbl_out[2], ev.tbl_out[3])
         e[s][4].record()
         for n, ms in zip(names[:4], ms4):

@@ -70,7 +70,7 @@ typedef struct {
   float tau1;              /* temperature of the dispersion H in Eq. 6 */
   float tau2;              /* temperature of the shift V in Eq. 6 */
   int32_t var_correction;  /* 1: unbiased Var over the S_w rows (divide by S_w-1); 0: biased */
-  int32_t pool_kernel;     /* odd width of the stride-1 max-pool over prefix positions; 1 = off */
+  int32_t pool_kernel;     /* odd width (<= 129) of the stride-1 max-pool over prefix positions; 1 = off */
 } cake_params;
 
 /* Library version (major*10000 + minor*100 + patch). */

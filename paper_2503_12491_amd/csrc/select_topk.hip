@@ -17,6 +17,7 @@ constexpr int kThreads = 1024;
 constexpr int kWaves = kThreads / 64;
 constexpr int kPerThread = 4;                       // consecutive entries per thread in the ordered pass
 constexpr int kTile = kThreads * kPerThread;
+constexpr int kBatch = 8;                           // loads in flight per thread in the histogram passes
 
 struct TopkArgs {
   const float* const* indicator;
@@ -51,9 +52,17 @@ __global__ __launch_bounds__(kThreads) void select_topk_kernel(TopkArgs a, Ragge
   for (int shift = 24; shift >= 0; shift -= 8) {
     if (tid < 256) hist[tid] = 0;
     __syncthreads();
-    for (int i = tid; i < cur; i += kThreads) {
-      uint32_t key = order_key(row[i]);
-      if ((key & mask) == prefix) atomicAdd(&hist[(key >> shift) & 0xFF], 1u);
+    // kBatch independent loads are in flight before the first histogram update, so that the
+    // pass runs at memory throughput rather than one load latency per element
+    for (int i0 = tid; i0 < cur; i0 += kThreads * kBatch) {
+      float x[kBatch];
+#pragma unroll
+      for (int u = 0; u < kBatch; ++u) x[u] = (i0 + u * kThreads < cur) ? row[i0 + u * kThreads] : 0.f;
+#pragma unroll
+      for (int u = 0; u < kBatch; ++u) {
+        const uint32_t key = order_key(x[u]);
+        if (i0 + u * kThreads < cur && (key & mask) == prefix) atomicAdd(&hist[(key >> shift) & 0xFF], 1u);
+      }
     }
     __syncthreads();
     if (wave == 0) {

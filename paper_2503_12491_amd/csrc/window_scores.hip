@@ -459,18 +459,30 @@ __global__ __launch_bounds__(512) void scores_pass2(ScoreArgs a) {
 }
 
 // Stride-1 max-pool over the prefix positions, edges clipped (Sec. 4.3 pooling layer).
-__global__ void pool_indicator(ScoreArgs a) {
+// A workgroup stages kPoolSpan consecutive positions plus the halo in LDS with coalesced loads,
+// so that every un-pooled value is read from memory once.
+constexpr int kPoolSpan = 2048;
+constexpr int kPoolMaxHalf = 64;        // widest supported pooling window: 2*64+1
+__global__ __launch_bounds__(256) void pool_indicator(ScoreArgs a) {
+  __shared__ float win[kPoolSpan + 2 * kPoolMaxHalf];
   const int slice = blockIdx.y;
   int l, b, g;
   slice_coords(a, slice, l, b, g);
-  const int j = blockIdx.x * blockDim.x + threadIdx.x;
-  if (j >= a.n_p) return;
-  const float* raw = a.raw + (int64_t)slice * a.n_p;
   const int half = a.pool / 2;
-  const int lo = max(j - half, 0), hi = min(j + half, a.n_p - 1);
-  float m = raw[lo];
-  for (int i = lo + 1; i <= hi; ++i) m = fmaxf(m, raw[i]);
-  a.indicator[l][((int64_t)b * a.h_kv + g) * a.n_p + j] = m;
+  const int j0 = blockIdx.x * kPoolSpan;
+  const float* raw = a.raw + (int64_t)slice * a.n_p;
+  const int lo = j0 - half, count = min(kPoolSpan, a.n_p - j0) + 2 * half;
+  for (int i = threadIdx.x; i < count; i += 256) {
+    const int j = lo + i;
+    win[i] = (j >= 0 && j < a.n_p) ? raw[j] : -INFINITY;     // clipped edges never win the max
+  }
+  __syncthreads();
+  float* out = a.indicator[l] + ((int64_t)b * a.h_kv + g) * a.n_p;
+  for (int i = threadIdx.x; i < kPoolSpan && j0 + i < a.n_p; i += 256) {
+    float m = win[i];
+    for (int k = 1; k <= 2 * half; ++k) m = fmaxf(m, win[i + k]);
+    out[j0 + i] = m;
+  }
 }
 
 // Eq. 6 per (layer, sequence): fixed-order fp64 reduction of the chunk sums, then the powers.
@@ -527,7 +539,7 @@ int launch_scores(const ScoreArgs& a, int64_t n_slices, hipStream_t stream) {
   mark(2, stream);
   hipLaunchKernelGGL((scores_pass2<T, D, MB>), dim3(a.n_chunks_p, (unsigned)n_slices), block, 0, stream, a);
   mark(3, stream);
-  hipLaunchKernelGGL(pool_indicator, dim3((a.n_p + 255) / 256, (unsigned)n_slices), dim3(256), 0, stream, a);
+  hipLaunchKernelGGL(pool_indicator, dim3((a.n_p + kPoolSpan - 1) / kPoolSpan, (unsigned)n_slices), dim3(256), 0, stream, a);
   mark(4, stream);
   if (g_profile.enabled && g_profile.created) g_profile.recorded = true;
   CAKE_HIP_TRY(hipGetLastError());
@@ -570,7 +582,8 @@ extern "C" int cake_window_scores(const cake_shape* shape, const cake_params* pa
   CAKE_REQUIRE(params != nullptr, "params is NULL");
   CAKE_REQUIRE(q_win && k && indicator, "q_win, k or indicator table is NULL");
   CAKE_REQUIRE(q_strides && k_strides, "q_strides or k_strides is NULL");
-  CAKE_REQUIRE(params->pool_kernel >= 1 && params->pool_kernel % 2 == 1, "pool_kernel %d must be odd and >= 1", params->pool_kernel);
+  CAKE_REQUIRE(params->pool_kernel >= 1 && params->pool_kernel % 2 == 1 && params->pool_kernel <= 2 * kPoolMaxHalf + 1,
+               "pool_kernel %d must be odd and within [1, %d]", params->pool_kernel, 2 * kPoolMaxHalf + 1);
   CAKE_REQUIRE(params->var_correction == 0 || params->var_correction == 1, "var_correction %d must be 0 or 1", params->var_correction);
   CAKE_REQUIRE(std::isfinite(params->gamma) && std::isfinite(params->scale) && params->scale >= 0.f, "gamma/scale must be finite, scale >= 0");
   const size_t eb = elem_bytes(shape->dtype);

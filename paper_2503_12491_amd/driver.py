@@ -77,6 +77,8 @@ class EvictionPass:
         self.pool_v = torch.empty_like(self.pool_k)
         self.pool_idx = torch.empty(bh * max(max_rows, 1), dtype=torch.int32, device=self.dev)
         self.pool_ind = torch.empty(bh * max(max_rows, 1), dtype=torch.float32, device=self.dev)
+        self._cur_full = [self.N_p] * (self.L * self.B)
+        self._strides_full = [_strides3(k0)] * self.L
         self.tbl_out_host = torch.empty(4, self.L, dtype=torch.int64).pin_memory()
         self.tbl_out = torch.empty(4, self.L, dtype=torch.int64, device=self.dev)
 
@@ -101,39 +103,51 @@ class EvictionPass:
         return out
 
     def _carve_outputs(self, keep: np.ndarray):
-        """Per-layer views of the output pools for the given keep counts [L, B]."""
-        caps = keep.max(axis=1)
+        """Place every layer's outputs in the pools for the given keep counts [L, B]: fills the
+        device pointer table (one asynchronous upload) and returns the per-layer element offsets.
+        No tensors are created here; `_views` makes them when a result is inspected."""
+        caps = keep.max(axis=1).astype(np.int64)
+        bh = self.B * self.H_kv
+        n_kv = bh * (caps + self.S_w) * self.d
+        n_i = bh * caps
+        off_kv = np.concatenate([[0], np.cumsum(n_kv)[:-1]])
+        off_i = np.concatenate([[0], np.cumsum(n_i)[:-1]])
+        th = self.tbl_out_host.numpy()
+        th[0] = self.pool_idx.data_ptr() + off_i * 4
+        th[1] = self.pool_k.data_ptr() + off_kv * self.pool_k.element_size()
+        th[2] = self.pool_v.data_ptr() + off_kv * self.pool_v.element_size()
+        th[3] = self.pool_ind.data_ptr() + off_i * 4
+        self.tbl_out.copy_(self.tbl_out_host, non_blocking=True)
+        return caps, off_kv, off_i
+
+    def _views(self, caps, off_kv, off_i):
+        """Per-layer tensor views of the output pools."""
         bh = self.B * self.H_kv
         idx, k_out, v_out, ind_out = [], [], [], []
-        off_kv = off_i = 0
-        th = self.tbl_out_host.numpy()
         for l in range(self.L):
-            cap = int(caps[l])
+            cap, okv, oi = int(caps[l]), int(off_kv[l]), int(off_i[l])
             n_kv = bh * (cap + self.S_w) * self.d
             n_i = bh * cap
-            k_out.append(self.pool_k[off_kv: off_kv + n_kv].view(self.B, self.H_kv, cap + self.S_w, self.d))
-            v_out.append(self.pool_v[off_kv: off_kv + n_kv].view(self.B, self.H_kv, cap + self.S_w, self.d))
-            idx.append(self.pool_idx[off_i: off_i + n_i].view(self.B, self.H_kv, cap))
-            ind_out.append(self.pool_ind[off_i: off_i + n_i].view(self.B, self.H_kv, cap))
-            th[0, l] = self.pool_idx.data_ptr() + off_i * 4
-            th[1, l] = self.pool_k.data_ptr() + off_kv * self.pool_k.element_size()
-            th[2, l] = self.pool_v.data_ptr() + off_kv * self.pool_v.element_size()
-            th[3, l] = self.pool_ind.data_ptr() + off_i * 4
-            off_kv += n_kv
-            off_i += n_i
-        self.tbl_out.copy_(self.tbl_out_host, non_blocking=True)
+            k_out.append(self.pool_k[okv: okv + n_kv].view(self.B, self.H_kv, cap + self.S_w, self.d))
+            v_out.append(self.pool_v[okv: okv + n_kv].view(self.B, self.H_kv, cap + self.S_w, self.d))
+            idx.append(self.pool_idx[oi: oi + n_i].view(self.B, self.H_kv, cap))
+            ind_out.append(self.pool_ind[oi: oi + n_i].view(self.B, self.H_kv, cap))
         return idx, k_out, v_out, ind_out
 
-    def evict(self, budgets: np.ndarray, stream=None):
+    def evict_launch(self, budgets: np.ndarray, stream=None):
+        """Top-k and compaction for all layers; returns (keep, placement) without touching the
+        outputs."""
         keep = np.minimum(np.maximum(budgets - self.S_w, 0), self.N_p)
-        idx, k_out, v_out, ind_out = self._carve_outputs(keep)
-        cur = [self.N_p] * (self.L * self.B)
-        kk = [int(x) for x in keep.reshape(-1)]
-        C.cake_select_topk(self.shape, self.tbl_ind, cur, kk, self.tbl_out[0], None, stream)
-        strides = [_strides3(self.k[0])] * self.L
-        C.cake_compact_kv(self.shape, self.tbl_k, self.tbl_v, strides, cur, kk, self.tbl_out[0], self.tbl_ind,
-                          self.tbl_out[1], self.tbl_out[2], self.tbl_out[3], stream)
-        return keep, idx, k_out, v_out, ind_out
+        placement = self._carve_outputs(keep)
+        kk = keep.reshape(-1).tolist()
+        C.cake_select_topk(self.shape, self.tbl_ind, self._cur_full, kk, self.tbl_out[0], None, stream)
+        C.cake_compact_kv(self.shape, self.tbl_k, self.tbl_v, self._strides_full, self._cur_full, kk, self.tbl_out[0],
+                          self.tbl_ind, self.tbl_out[1], self.tbl_out[2], self.tbl_out[3], stream)
+        return keep, placement
+
+    def evict(self, budgets: np.ndarray, stream=None):
+        keep, placement = self.evict_launch(budgets, stream)
+        return (keep,) + self._views(*placement)
 
     # ------------------------------------------------------------------ whole pass
     def run(self) -> PassResult:
@@ -144,6 +158,13 @@ class EvictionPass:
         keep, idx, k_out, v_out, ind_out = self.evict(budgets)
         return PassResult(budgets, keep, pref, hv, [self.indicator[l] for l in range(self.L)], idx, k_out, v_out,
                           ind_out)
+
+    def run_launch_only(self):
+        """The same pass without building result views (what a serving loop, and bench.py, time)."""
+        self.scores()
+        pref, hv = self.preferences_to_host()
+        budgets = self.allocate(pref)
+        return self.evict_launch(budgets)
 
     def run_cascade(self, track_positions: bool = True) -> PassResult:
         """Cascading pass (Sec. 4.2, Alg. 1).  Stage m scores layer m, recomputes B^(m) over the
