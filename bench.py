@@ -22,6 +22,10 @@ sys.path.insert(0, ROOT)
 HBM_PEAK_GBPS = 8000.0          # MI355X HBM3E
 MFMA_BF16_PEAK_TFLOPS = 2500.0  # dense bf16
 MFMA_F32_PEAK_TFLOPS = 157.3
+VALU_F32_PEAK_TFLOPS = 78.6     # fp32 vector FMA rate without packed instructions (half of 157.3)
+# Vector-ALU issue slots per logit that the arithmetic itself needs (simple op = 1, exp = 2):
+# pass 1: fma, exp, add; pass 2: fma, exp, add, fma, fma.
+VALU_SLOTS_PER_LOGIT = {"scores_pass1": 4, "scores_pass2": 6}
 
 
 def parse_args():
@@ -48,7 +52,8 @@ def cpu_baseline(cfg, layer_inputs, params):
     except Exception:
         threads = os.cpu_count() or 1
     p = co.OracleParams(scale=None, gamma=params.gamma, tau1=params.tau1, tau2=params.tau2,
-                        var_correction=params.var_correction, pool_kernel=params.pool_kernel)
+                        var_correction=params.var_correction, pool_kernel=params.pool_kernel,
+                        indicator_mode=params.indicator_mode)
     group = cfg.n_q_heads // cfg.n_kv_heads
     q = layer_inputs["q_win"].double().cpu().numpy()
     heads_done, t_total = 0, 0.0
@@ -196,8 +201,19 @@ def main():
     group = cfg.n_q_heads // cfg.n_kv_heads
     flops_pass = 2.0 * tokens_layers * cfg.n_q_heads * cfg.window * cfg.head_dim   # one logits pass
     achieved = alg[dominant] / dom_s / 1e9
-    roofline = {"kernel": dominant, "bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBPS, "unit": "GB/s",
-                "frac": achieved / HBM_PEAK_GBPS, "traffic": measured_traffic(cfg, dominant)}
+    hbm_view = {"achieved": achieved, "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBPS}
+    if dominant in VALU_SLOTS_PER_LOGIT:
+        # The score passes are bound by vector-ALU issue, not by HBM.
+        # One issue slot = one wave-wide fp32 instruction = 64 lanes x 2 flop (an FMA); v_exp_f32
+        # takes two slots.  Peak = 256 CUs x 4 SIMDs x 2.4 GHz / 4 cycles per slot = 78.6 TFLOP/s,
+        # the fp32 vector peak without packed instructions (disabled on this pool).
+        logits = tokens_layers * cfg.n_q_heads * cfg.window
+        tflops = logits * VALU_SLOTS_PER_LOGIT[dominant] * 2.0 / dom_s / 1e12
+        roofline = {"kernel": dominant, "bound": "alu", "achieved": tflops, "peak": VALU_F32_PEAK_TFLOPS,
+                    "unit": "TFLOP/s", "frac": tflops / VALU_F32_PEAK_TFLOPS,
+                    "traffic": measured_traffic(cfg, dominant), "hbm": hbm_view}
+    else:
+        roofline = {"kernel": dominant, "bound": "hbm", **hbm_view, "traffic": measured_traffic(cfg, dominant)}
     mfma_peak = MFMA_BF16_PEAK_TFLOPS if cfg.dtype == "bf16" else MFMA_F32_PEAK_TFLOPS
     extra = {
         "kernel_ms": {n: round(v, 4) for n, v in kernel_ms.items()},

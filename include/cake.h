@@ -63,6 +63,16 @@ typedef struct {
   int32_t dtype;       /* cake_dtype of Q, K, V */
 } cake_shape;
 
+/* Per-head token score before the group mean and the pooling.  CAKE's own indicator is
+ * Mean + gamma*Var (Sec. 4.3 Eq. 11); the other three are the alternatives of the paper's
+ * indicator ablation (Sec. 5, "Effectiveness of Proposed Eviction Indicator"). */
+typedef enum {
+  CAKE_IND_MEAN_PLUS_VAR = 0,  /* Mean + gamma*Var */
+  CAKE_IND_MEAN = 1,           /* Mean (the SnapKV-style window mean) */
+  CAKE_IND_VAR = 2,            /* Var */
+  CAKE_IND_MEAN_TIMES_VAR = 3  /* Mean * Var */
+} cake_indicator;
+
 /* Method parameters (Sec. 4.1 Eq. 6, Sec. 4.3 Eq. 11 and the implementation appendix). */
 typedef struct {
   float scale;             /* softmax scale; 0 selects 1/sqrt(head_dim) (Sec. 2) */
@@ -71,6 +81,7 @@ typedef struct {
   float tau2;              /* temperature of the shift V in Eq. 6 */
   int32_t var_correction;  /* 1: unbiased Var over the S_w rows (divide by S_w-1); 0: biased */
   int32_t pool_kernel;     /* odd width (<= 129) of the stride-1 max-pool over prefix positions; 1 = off */
+  int32_t indicator_mode;  /* cake_indicator: which per-head statistic scores a token */
 } cake_params;
 
 /* Library version (major*10000 + minor*100 + patch). */

@@ -48,6 +48,7 @@ class OracleParams:
     tau2: float = 1.0
     var_correction: int = 1
     pool_kernel: int = 7
+    indicator_mode: int = 0         # 0 Mean + gamma*Var (Eq. 11); 1 Mean; 2 Var; 3 Mean*Var (indicator ablation)
 
 
 # ----------------------------------------------------------------------------------------
@@ -123,11 +124,21 @@ def layer_preference(h_heads: np.ndarray, v_heads: np.ndarray, tau1: float = 1.0
 # ----------------------------------------------------------------------------------------
 # Attention-shift tolerant eviction indicator (Sec. 4.3)
 # ----------------------------------------------------------------------------------------
-def head_indicator(a_obs: np.ndarray, gamma: float, var_correction: int = 1) -> np.ndarray:
-    """Eq. (11), prefix case: Mean(A[-S_w:, n]) + gamma * Var(A[-S_w:, n]).  [H_q, N_p]"""
+def head_indicator(a_obs: np.ndarray, gamma: float, var_correction: int = 1, mode: int = 0) -> np.ndarray:
+    """Eq. (11), prefix case: Mean(A[-S_w:, n]) + gamma * Var(A[-S_w:, n]).  [H_q, N_p]
+    Modes 1-3 are the alternatives of the paper's indicator ablation: Mean, Var, Mean * Var."""
     s_w = a_obs.shape[-2]
     mean = np.sum(a_obs, axis=-2) / s_w
-    return mean + gamma * column_variance(a_obs, var_correction)
+    var = column_variance(a_obs, var_correction)
+    if mode == 0:
+        return mean + gamma * var
+    if mode == 1:
+        return mean
+    if mode == 2:
+        return var
+    if mode == 3:
+        return mean * var
+    raise ValueError("indicator mode")
 
 
 def group_reduce(i_q: np.ndarray, group: int) -> np.ndarray:
@@ -152,7 +163,7 @@ def max_pool(x: np.ndarray, width: int) -> np.ndarray:
 def eviction_indicator(a_obs: np.ndarray, group: int, p: OracleParams) -> np.ndarray:
     """I[g, n] for prefix positions n < N - S_w.  The window positions carry Omega in
     Eq. (11): they are always retained and are not part of this array."""
-    i_q = head_indicator(a_obs, p.gamma, p.var_correction)
+    i_q = head_indicator(a_obs, p.gamma, p.var_correction, p.indicator_mode)
     return max_pool(group_reduce(i_q, group), p.pool_kernel)
 
 

@@ -14,7 +14,8 @@ class cake_shape(ctypes.Structure):
 
 class cake_params(ctypes.Structure):
     _fields_ = [("scale", ctypes.c_float), ("gamma", ctypes.c_float), ("tau1", ctypes.c_float),
-                ("tau2", ctypes.c_float), ("var_correction", ctypes.c_int32), ("pool_kernel", ctypes.c_int32)]
+                ("tau2", ctypes.c_float), ("var_correction", ctypes.c_int32), ("pool_kernel", ctypes.c_int32),
+                ("indicator_mode", ctypes.c_int32)]
 
 
 _P = ctypes.c_void_p

@@ -28,8 +28,12 @@ def make_shape(batch, n_layers, n_q_heads, n_kv_heads, head_dim, seq_len, window
     return cake_shape(batch, n_layers, n_q_heads, n_kv_heads, head_dim, seq_len, window, dtype)
 
 
-def make_params(scale=0.0, gamma=200.0, tau1=1.0, tau2=1.0, var_correction=1, pool_kernel=7) -> cake_params:
-    return cake_params(scale, gamma, tau1, tau2, var_correction, pool_kernel)
+CAKE_IND_MEAN_PLUS_VAR, CAKE_IND_MEAN, CAKE_IND_VAR, CAKE_IND_MEAN_TIMES_VAR = 0, 1, 2, 3
+
+
+def make_params(scale=0.0, gamma=200.0, tau1=1.0, tau2=1.0, var_correction=1, pool_kernel=7,
+                indicator_mode=CAKE_IND_MEAN_PLUS_VAR) -> cake_params:
+    return cake_params(scale, gamma, tau1, tau2, var_correction, pool_kernel, indicator_mode)
 
 
 def ptr_table(tensors: Sequence[torch.Tensor]) -> torch.Tensor:

@@ -90,7 +90,8 @@ struct ScoreArgs {
   int64_t qs[3], ks[3];      // element strides: batch, head, token
   int32_t batch, h_kv, group, n, n_p, chunk, n_chunks, n_chunks_p, pool;
   float c;                   // scale * log2(e): logits are handled in the log2 domain
-  float gamma, inv_sw, inv_swc, inv_g;
+  float inv_sw, inv_swc, inv_g;
+  float w_mean, w_var, w_prod;   // I_q = w_mean*Mean + w_var*Var + w_prod*Mean*Var (Eq. 11 and the ablation's variants)
   float* lse;                // [slice][G*S_w]
   float* part;               // [slice][n_chunks][G*S_w][2]
   float* hv;                 // [slice][n_chunks_p][G][2]
@@ -371,7 +372,8 @@ __device__ __forceinline__ void pass2_subtile(const char* tile, int sub, int kb,
     ent_acc += ent;
     if (hh == 0) var_acc += var;
   }
-  if (hh == 0) iq_row[sub * 32 + c32] = valid ? mean + a.gamma * var : 0.f;
+  const float iq = fmaf(a.w_prod * mean, var, fmaf(a.w_var, var, a.w_mean * mean));
+  if (hh == 0) iq_row[sub * 32 + c32] = valid ? iq : 0.f;
 }
 
 template <typename T, int D, int MB>
@@ -584,6 +586,8 @@ extern "C" int cake_window_scores(const cake_shape* shape, const cake_params* pa
   CAKE_REQUIRE(q_strides && k_strides, "q_strides or k_strides is NULL");
   CAKE_REQUIRE(params->pool_kernel >= 1 && params->pool_kernel % 2 == 1 && params->pool_kernel <= 2 * kPoolMaxHalf + 1,
                "pool_kernel %d must be odd and within [1, %d]", params->pool_kernel, 2 * kPoolMaxHalf + 1);
+  CAKE_REQUIRE(params->indicator_mode >= CAKE_IND_MEAN_PLUS_VAR && params->indicator_mode <= CAKE_IND_MEAN_TIMES_VAR,
+               "indicator_mode %d is not a cake_indicator", params->indicator_mode);
   CAKE_REQUIRE(params->var_correction == 0 || params->var_correction == 1, "var_correction %d must be 0 or 1", params->var_correction);
   CAKE_REQUIRE(std::isfinite(params->gamma) && std::isfinite(params->scale) && params->scale >= 0.f, "gamma/scale must be finite, scale >= 0");
   const size_t eb = elem_bytes(shape->dtype);
@@ -606,9 +610,12 @@ extern "C" int cake_window_scores(const cake_shape* shape, const cake_params* pa
   a.batch = shape->batch; a.h_kv = shape->n_kv_heads; a.group = shape->n_q_heads / shape->n_kv_heads;
   a.n = shape->seq_len; a.n_p = shape->seq_len - shape->window;
   a.chunk = lay.chunk; a.n_chunks = lay.n_chunks; a.n_chunks_p = lay.n_chunks_p; a.pool = params->pool_kernel;
+  const int mode = params->indicator_mode;     // Eq. 11, or Mean, Var, Mean*Var of the indicator ablation
+  a.w_mean = (mode == CAKE_IND_MEAN_PLUS_VAR || mode == CAKE_IND_MEAN) ? 1.f : 0.f;
+  a.w_var = mode == CAKE_IND_MEAN_PLUS_VAR ? params->gamma : mode == CAKE_IND_VAR ? 1.f : 0.f;
+  a.w_prod = mode == CAKE_IND_MEAN_TIMES_VAR ? 1.f : 0.f;
   const double scale = params->scale > 0.f ? (double)params->scale : 1.0 / std::sqrt((double)shape->head_dim);
   a.c = (float)(scale * 1.4426950408889634);
-  a.gamma = params->gamma;
   a.inv_sw = 1.0f / (float)shape->window;
   a.inv_swc = 1.0f / (float)(shape->window - params->var_correction);
   a.inv_g = 1.0f / (float)a.group;

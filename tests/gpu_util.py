@@ -28,7 +28,8 @@ def say(msg):
 
 def oracle_params(params) -> co.OracleParams:
     return co.OracleParams(scale=(params.scale if params.scale > 0 else None), gamma=params.gamma, tau1=params.tau1,
-                           tau2=params.tau2, var_correction=params.var_correction, pool_kernel=params.pool_kernel)
+                           tau2=params.tau2, var_correction=params.var_correction, pool_kernel=params.pool_kernel,
+                           indicator_mode=params.indicator_mode)
 
 
 def host64(t: torch.Tensor) -> np.ndarray:

@@ -72,6 +72,40 @@ def test_worked_example_gqa_pool_and_preference():
     np.testing.assert_allclose(co.layer_pass(q, k, p3)["indicator"][0], [max(want)] * 2, rtol=1e-13)
 
 
+@pytest.mark.parametrize("head", ["head0", "head1"])
+def test_worked_example_indicator_ablation_modes(head):
+    """Indicator ablation (Mean, Var, Mean*Var beside Mean + gamma*Var): each mode against the
+    rationals of the worked example, and the GQA mean taken on the per-head values."""
+    g, q, k = _example_inputs([head])
+    a_obs = co.observed(co.window_attention(q, k, scale=1.0), 2)
+    mean = [Fraction(x) for x in g[head]["mean"]]
+    var = [Fraction(x) for x in g[head]["var_unbiased"]]
+    np.testing.assert_allclose(co.head_indicator(a_obs, 200.0, 1, mode=1)[0], [float(m) for m in mean], rtol=1e-13)
+    np.testing.assert_allclose(co.head_indicator(a_obs, 200.0, 1, mode=2)[0], [float(v) for v in var], rtol=1e-13)
+    np.testing.assert_allclose(co.head_indicator(a_obs, 200.0, 1, mode=3)[0],
+                               [float(m * v) for m, v in zip(mean, var)], rtol=1e-13)
+    np.testing.assert_allclose(co.head_indicator(a_obs, 200.0, 1, mode=0)[0],
+                               [float(m + 200 * v) for m, v in zip(mean, var)], rtol=1e-13)
+    with pytest.raises(ValueError):
+        co.head_indicator(a_obs, 200.0, 1, mode=4)
+
+
+def test_indicator_modes_through_layer_pass():
+    g, q, k = _example_inputs(["head0", "head1"])
+    m = [[Fraction(x) for x in g[h]["mean"]] for h in ("head0", "head1")]
+    v = [[Fraction(x) for x in g[h]["var_unbiased"]] for h in ("head0", "head1")]
+    want = {1: [(m[0][j] + m[1][j]) / 2 for j in range(2)],
+            2: [(v[0][j] + v[1][j]) / 2 for j in range(2)],
+            3: [(m[0][j] * v[0][j] + m[1][j] * v[1][j]) / 2 for j in range(2)]}   # product per head, then the group mean
+    for mode, w in want.items():
+        p = co.OracleParams(scale=1.0, pool_kernel=1, indicator_mode=mode)
+        np.testing.assert_allclose(co.layer_pass(q, k, p)["indicator"][0], [float(x) for x in w], rtol=1e-13)
+    # the mean-only mode is what gamma = 0 gives in Eq. (11)
+    p0 = co.OracleParams(scale=1.0, gamma=0.0, pool_kernel=1)
+    p1 = co.OracleParams(scale=1.0, pool_kernel=1, indicator_mode=1)
+    np.testing.assert_array_equal(co.layer_pass(q, k, p0)["indicator"], co.layer_pass(q, k, p1)["indicator"])
+
+
 # ---------------------------------------------------------------- softmax
 def test_softmax_rows_sum_to_one_and_match_scipy():
     rng = np.random.default_rng(0)

@@ -274,6 +274,16 @@ def test_pass_batch_has_per_sequence_budgets(cake):
     assert res.budgets.shape == (3, 2)
 
 
+@pytest.mark.parametrize("mode", [1, 2, 3])
+def test_pass_indicator_ablation_modes(cake, mode):
+    # Mean, Var and Mean*Var in place of Mean + gamma*Var (the paper's indicator ablation)
+    say(f"pass indicator mode {mode}")
+    cfg = CONFIGS[2].scaled(n_layers=2, seq_len=2048 + 32 + 19, total_budget=2 * 400)
+    _check_pass(cake, cfg, cake.make_params(indicator_mode=mode))
+    cfg = CONFIGS[4].scaled(n_layers=1, seq_len=1500, total_budget=300)
+    _check_pass(cake, cfg, cake.make_params(indicator_mode=mode, pool_kernel=1))
+
+
 def test_pass_is_deterministic(cake):
     say("pass determinism")
     cfg = CONFIGS[2].scaled(n_layers=2, seq_len=3000, total_budget=2 * 300)
