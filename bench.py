@@ -36,6 +36,9 @@ def parse_args():
     ap.add_argument("--config", type=int, default=4, help="synthetic config id (4 = 128K context, the headline)")
     ap.add_argument("--layers", type=int, default=0, help="override layer count (0 = the config's)")
     ap.add_argument("--no-cpu-baseline", action="store_true", help="skip the oracle timing (profiling runs)")
+    ap.add_argument("--row-lse", action="store_true",
+                    help="variant: hand the window rows' log-sum-exp to the library (cake_window_scores_lse), "
+                         "as a prefill attention kernel would; the scores then read K once")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also run a plain 1 GiB device copy four times (reference for the HBM byte counters)")
     return ap.parse_args()
@@ -130,8 +133,21 @@ def main():
             del one
     torch.cuda.synchronize()
     params = cake.make_params()
+    row_lse = None
+    if args.row_lse:
+        # stand-in for the normalisers a prefill attention kernel returns: torch, one layer at a time
+        row_lse = []
+        G = cfg.n_q_heads // cfg.n_kv_heads
+        pos_q = cfg.prefix_len + torch.arange(cfg.window, device=dev)
+        for l in range(L):
+            qf = q_all[l].float().view(B, cfg.n_kv_heads, G * cfg.window, cfg.head_dim) * cfg.head_dim ** -0.5
+            s_ = torch.matmul(qf, k_all[l].float().transpose(-1, -2)).view(B, cfg.n_q_heads, cfg.window, cfg.seq_len)
+            tail = s_[..., cfg.prefix_len:]
+            tail.masked_fill_(torch.arange(cfg.prefix_len, cfg.seq_len, device=dev)[None, :] > pos_q[:, None], float("-inf"))
+            row_lse.append(torch.logsumexp(s_, dim=-1).contiguous())
+            del qf, s_, tail
     ev = cake.EvictionPass([q_all[l] for l in range(L)], [k_all[l] for l in range(L)], [v_all[l] for l in range(L)],
-                           cfg.total_budget, params)
+                           cfg.total_budget, params, row_lse=row_lse)
 
     if args.copy_calibration:
         src = torch.empty(1 << 30, dtype=torch.uint8, device=dev).fill_(1)
@@ -147,7 +163,8 @@ def main():
 
     # ---- timed region: exactly `steps` passes, per-kernel HIP events on the launch stream ----
     cake.cake_profile_enable(True)
-    names = ["scores_pass1", "scores_combine", "scores_pass2", "pool_indicator", "layer_preference",
+    first = "scores_pass1" if not args.row_lse else "scores_import_lse"
+    names = [first, "scores_combine", "scores_pass2", "pool_indicator", "layer_preference",
              "select_topk", "compact_kv"]
     kernel_ms = {n: 0.0 for n in names}
     e = [[torch.cuda.Event(enable_timing=True) for _ in range(5)] for _ in range(args.steps)]
@@ -156,7 +173,11 @@ def main():
     q_str = [q_all[0].stride(i) for i in range(3)]
     k_str = [k_all[0].stride(i) for i in range(3)]
     for s in range(args.steps):
-        cake.cake_window_scores(ev.shape, ev.params, ev.tbl_q, ev.tbl_k, q_str, k_str, ev.tbl_ind, ev.workspace)
+        if row_lse is None:
+            cake.cake_window_scores(ev.shape, ev.params, ev.tbl_q, ev.tbl_k, q_str, k_str, ev.tbl_ind, ev.workspace)
+        else:
+            cake.cake_window_scores_lse(ev.shape, ev.params, ev.tbl_q, ev.tbl_k, q_str, k_str, ev.tbl_lse, ev.tbl_ind,
+                                        ev.workspace)
         e[s][0].record()
         cake.cake_layer_preference(ev.shape, ev.params, ev.workspace, ev.pref, ev.hv)
         e[s][1].record()
@@ -193,9 +214,9 @@ def main():
     ind_bytes = n_rows * cfg.prefix_len * 4
     kept_rows = int((keep.sum() + L * B * cfg.window) * cfg.n_kv_heads)
     compact_bytes = kept_rows * cfg.head_dim * eb * 2 * 2                            # K and V, read + write
-    alg = {"scores_pass1": k_bytes, "scores_pass2": k_bytes + ind_bytes, "pool_indicator": 2 * ind_bytes,
+    alg = {"scores_pass1": k_bytes, "scores_import_lse": 0, "scores_pass2": k_bytes + ind_bytes, "pool_indicator": 2 * ind_bytes,
            "select_topk": 4 * ind_bytes, "compact_kv": compact_bytes, "scores_combine": 0, "layer_preference": 0}
-    pass_alg_bytes = k_bytes + ind_bytes * 7 + compact_bytes
+    pass_alg_bytes = k_bytes + ind_bytes * 7 + compact_bytes        # K counted once: the second read is the method's choice
     dominant = max(kernel_ms, key=kernel_ms.get)
     dom_s = kernel_ms[dominant] * 1e-3
     group = cfg.n_q_heads // cfg.n_kv_heads
@@ -215,12 +236,13 @@ def main():
     else:
         roofline = {"kernel": dominant, "bound": "hbm", **hbm_view, "traffic": measured_traffic(cfg, dominant)}
     mfma_peak = MFMA_BF16_PEAK_TFLOPS if cfg.dtype == "bf16" else MFMA_F32_PEAK_TFLOPS
+    score_passes = [n for n in ("scores_pass1", "scores_pass2") if n in kernel_ms]
     extra = {
         "kernel_ms": {n: round(v, 4) for n, v in kernel_ms.items()},
         "pass_algorithmic_GBps": pass_alg_bytes / (elapsed / args.steps) / 1e9,
         "pass_hbm_frac": pass_alg_bytes / (elapsed / args.steps) / 1e9 / HBM_PEAK_GBPS,
-        "score_mfma_TFLOPs": {n: flops_pass / (kernel_ms[n] * 1e-3) / 1e12 for n in ("scores_pass1", "scores_pass2")},
-        "score_mfma_frac": {n: flops_pass / (kernel_ms[n] * 1e-3) / 1e12 / mfma_peak for n in ("scores_pass1", "scores_pass2")},
+        "score_mfma_TFLOPs": {n: flops_pass / (kernel_ms[n] * 1e-3) / 1e12 for n in score_passes},
+        "score_mfma_frac": {n: flops_pass / (kernel_ms[n] * 1e-3) / 1e12 / mfma_peak for n in score_passes},
         "host_and_gaps_ms": ms_per_step - sum(kernel_ms.values()),
     }
 
@@ -231,7 +253,7 @@ def main():
         "dtype": cfg.dtype, "data": "synthetic",
         "config": {"workload": f"config {cfg.cid} ({cfg.name}): L={L} H_q={cfg.n_q_heads} H_kv={cfg.n_kv_heads} "
                                f"d={cfg.head_dim} N={cfg.seq_len} S_w={cfg.window} B={B} B_total={cfg.total_budget} "
-                               f"one-shot pass", "gamma": params.gamma, "tau1": params.tau1, "tau2": params.tau2,
+                               f"one-shot pass" + (", row LSE handed over (K read once)" if args.row_lse else ""), "gamma": params.gamma, "tau1": params.tau1, "tau2": params.tau2,
                    "pool_kernel": params.pool_kernel},
         "roofline": roofline, "stages": extra,
     }

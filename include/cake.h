@@ -90,7 +90,7 @@ int cake_version(void);
 /* Reason for the calling thread's most recent failure; "" if none. */
 const char* cake_last_error(void);
 
-/* Bytes of device workspace that cake_window_scores, cake_layer_preference and
+/* Bytes of device workspace that cake_window_scores(_lse), cake_layer_preference and
  * cake_select_topk need for `shape` (the maximum over the three).  The workspace must be
  * 256-byte aligned.  cake_layer_preference reads what cake_window_scores left in it, so the
  * same buffer must be passed to both with nothing else written in between. */
@@ -119,6 +119,23 @@ int cake_window_scores(const cake_shape* shape, const cake_params* params,
                        const int64_t* q_strides, const int64_t* k_strides,
                        float* const* indicator,
                        void* workspace, size_t workspace_bytes, void* stream);
+
+/*
+ * The same scores when the softmax normaliser of every window row is already known: the
+ * prefill attention that the model runs anyway (the paper's implementation calls a
+ * FlashAttention forward, App. "More implementation details") returns the log-sum-exp of each
+ * query row, so the pass over the keys that would recompute it is skipped and K is read once.
+ *
+ *   row_lse    table; row_lse[l] -> [B, H_q, S_w] f32, contiguous: for window row r of head h the
+ *              natural logarithm of sum_{j <= N_p + r} exp(scale * <q_r, k_j>), with the same
+ *              `scale` as params.  An error of e in an entry scales that row's weights by exp(-e).
+ * Everything else as in cake_window_scores; results agree with it to rounding when row_lse is exact.
+ */
+int cake_window_scores_lse(const cake_shape* shape, const cake_params* params,
+                           const void* const* q_win, const void* const* k,
+                           const int64_t* q_strides, const int64_t* k_strides,
+                           const float* const* row_lse, float* const* indicator,
+                           void* workspace, size_t workspace_bytes, void* stream);
 
 /*
  * Layer preference (Sec. 4.1 Eq. 6): H_l and V_l are the means over the layer's query heads

@@ -86,6 +86,14 @@ def window_attention(q_win, k, scale=None) -> np.ndarray:
     return softmax_rows(window_logits(q_win, k, scale))
 
 
+def window_attention_given_lse(q_win, k, row_lse: np.ndarray, scale=None) -> np.ndarray:
+    """A[h, r, j] = exp(s[h, r, j] - lse[h, r]) with the rows' log-sum-exp supplied by the caller
+    (natural log), the form the softmax of Sec. 2 takes once its denominator is known; hidden keys
+    get weight 0.  Equals window_attention when lse[h, r] = ln sum_j exp(s[h, r, j])."""
+    s = window_logits(q_win, k, scale)
+    return np.exp(s - np.asarray(row_lse, dtype=np.float64)[..., None])
+
+
 def observed(a: np.ndarray, window: int) -> np.ndarray:
     """A[-S_w:, :-S_w] of Eq. (6): the window queries' weights on the prefix keys."""
     return a[..., : a.shape[-1] - window]
@@ -167,8 +175,9 @@ def eviction_indicator(a_obs: np.ndarray, group: int, p: OracleParams) -> np.nda
     return max_pool(group_reduce(i_q, group), p.pool_kernel)
 
 
-def layer_pass(q_win, k, p: OracleParams) -> dict:
-    """Everything one layer contributes before allocation: indicator [H_kv,N_p], H_h, V_h, P."""
+def layer_pass(q_win, k, p: OracleParams, row_lse: Optional[np.ndarray] = None) -> dict:
+    """Everything one layer contributes before allocation: indicator [H_kv,N_p], H_h, V_h, P.
+    With row_lse [H_q, S_w] the rows are normalised by the supplied log-sum-exp instead."""
     q_win = np.asarray(q_win, dtype=np.float64)
     k = np.asarray(k, dtype=np.float64)
     h_q, s_w, _ = q_win.shape
@@ -179,7 +188,11 @@ def layer_pass(q_win, k, p: OracleParams) -> dict:
     v_heads = np.empty(h_q)
     for g in range(h_kv):                       # one KV group at a time only to bound memory
         heads = slice(g * group, (g + 1) * group)
-        a_obs = observed(window_attention(q_win[heads], k[g: g + 1], p.scale), s_w)
+        if row_lse is None:
+            a_full = window_attention(q_win[heads], k[g: g + 1], p.scale)
+        else:
+            a_full = window_attention_given_lse(q_win[heads], k[g: g + 1], np.asarray(row_lse)[heads], p.scale)
+        a_obs = observed(a_full, s_w)
         h_heads[heads] = dispersion(a_obs)
         v_heads[heads] = shift(a_obs, p.var_correction)
         ind[g] = eviction_indicator(a_obs, group, p)[0]

@@ -26,6 +26,9 @@ _SIGNATURES = {
     "cake_window_scores": (ctypes.c_int, [ctypes.POINTER(cake_shape), ctypes.POINTER(cake_params), _P, _P,
                                           ctypes.POINTER(ctypes.c_int64), ctypes.POINTER(ctypes.c_int64), _P,
                                           _P, ctypes.c_size_t, _P]),
+    "cake_window_scores_lse": (ctypes.c_int, [ctypes.POINTER(cake_shape), ctypes.POINTER(cake_params), _P, _P,
+                                              ctypes.POINTER(ctypes.c_int64), ctypes.POINTER(ctypes.c_int64), _P, _P,
+                                              _P, ctypes.c_size_t, _P]),
     "cake_layer_preference": (ctypes.c_int, [ctypes.POINTER(cake_shape), ctypes.POINTER(cake_params), _P,
                                              ctypes.c_size_t, _P, _P, _P]),
     "cake_cascade_allocate": (ctypes.c_int, [ctypes.POINTER(ctypes.c_double), ctypes.c_int32, ctypes.c_int64,

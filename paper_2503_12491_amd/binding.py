@@ -82,6 +82,14 @@ def cake_window_scores(shape, params, q_win, k, q_strides, k_strides, indicator,
                                      workspace.numel() * workspace.element_size(), _stream(stream)))
 
 
+def cake_window_scores_lse(shape, params, q_win, k, q_strides, k_strides, row_lse, indicator, workspace,
+                           stream=None) -> None:
+    _check(load().cake_window_scores_lse(ctypes.byref(shape), ctypes.byref(params), _ptr(q_win), _ptr(k),
+                                         _i64(q_strides), _i64(k_strides), _ptr(row_lse), _ptr(indicator),
+                                         _ptr(workspace), workspace.numel() * workspace.element_size(),
+                                         _stream(stream)))
+
+
 def cake_layer_preference(shape, params, workspace, pref, hv=None, stream=None) -> None:
     _check(load().cake_layer_preference(ctypes.byref(shape), ctypes.byref(params), _ptr(workspace),
                                         workspace.numel() * workspace.element_size(), _ptr(pref), _ptr(hv),
@@ -115,7 +123,8 @@ def cake_profile_enable(enable: bool) -> None:
 
 
 def cake_profile_read() -> list:
-    """Milliseconds of the last cake_window_scores call: [pass 1, combine, pass 2, pooling]."""
+    """Milliseconds of the last cake_window_scores call: [pass 1, combine, pass 2, pooling]
+    (with handed-over normalisers: [their import, 0, pass 2, pooling])."""
     out = (ctypes.c_float * 4)()
     _check(load().cake_profile_read(out))
     return list(out)

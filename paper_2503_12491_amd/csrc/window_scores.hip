@@ -101,17 +101,17 @@ struct ScoreArgs {
 // Transfer of keys [t0, t0+64) of one slice into an LDS tile.  The tile is moved as 1 KiB
 // groups, one wave-wide instruction each, group i by wave i mod G.  Lane j of a group fills LDS
 // bytes [16 j, 16 j + 16) of that group and fetches the piece of the key row that the swizzle
-// assigns to that place.  The per-lane part of the source offset takes only kVariants distinct
-// values (the swizzle repeats every kPieces rows), which are computed once per kernel; per
-// transfer there remain a scalar base and one select.  Rows past the last key are clamped to it
-// (their logits are masked later), so every access stays inside the slice.
+// assigns to that place: group i holds rows i*kRows + lr (lr = j / kPieces), and since kRows is a
+// power of two the swizzle splits into a per-lane part (slot ^ lr) and a per-group part
+// (i*kRows mod kPieces) that is XORed in with one instruction.  The per-lane offsets are computed
+// once per kernel; per transfer there remain a scalar base, one XOR and one add, and no branch.
+// Rows past the last key are clamped to it (their logits are masked later), so every access
+// stays inside the slice.
 template <typename T, int D>
 struct TileMover {
   using TL = Tile<T, D>;
   static constexpr int kRows = 1024 / TL::kRowBytes;                           // key rows per group
-  static constexpr int kVariants = TL::kPieces > kRows ? TL::kPieces / kRows : 1;
-  static constexpr bool kFast = kVariants <= 4;
-  uint32_t off0, off1, off2, off3;          // per-lane source offsets of the (at most four) variants
+  uint32_t row_off, piece_off;              // per-lane: lr * token stride; (slot ^ lr) * 16
   const char* kbase;
   int64_t tok_bytes;
   int last_key, wave, n_waves, lane;
@@ -120,19 +120,15 @@ struct TileMover {
                                        int lane_) {
     kbase = kbase_; tok_bytes = tok_bytes_; last_key = last_key_; wave = wave_; n_waves = n_waves_; lane = lane_;
     const int lr = lane / TL::kPieces, slot = lane % TL::kPieces;
-    auto variant = [&](int m) {
-      const int q = slot ^ ((m * kRows + lr) & (TL::kPieces - 1));
-      return (uint32_t)(lr * tok_bytes + q * 16);
-    };
-    off0 = variant(0); off1 = variant(1 % kVariants); off2 = variant(2 % kVariants); off3 = variant(3 % kVariants);
+    row_off = (uint32_t)(lr * tok_bytes);
+    piece_off = (uint32_t)((slot ^ lr) << 4);
   }
   __device__ __forceinline__ void issue(char* tile, int t0) const {
-    if (kFast && t0 + kTileKeys - 1 <= last_key) {       // whole tile inside the slice
+    if (t0 + kTileKeys - 1 <= last_key) {       // whole tile inside the slice
       const char* base = kbase + (int64_t)t0 * tok_bytes;
       for (int i = wave; i < TL::kGroups; i += n_waves) {
-        const int m = i % kVariants;
-        const uint32_t off = m == 0 ? off0 : m == 1 ? off1 : m == 2 ? off2 : off3;
-        const char* src = base + (int64_t)i * kRows * tok_bytes + off;
+        const uint32_t group_bits = (uint32_t)(((i * kRows) & (TL::kPieces - 1)) << 4);
+        const char* src = base + (int64_t)i * kRows * tok_bytes + (row_off + (piece_off ^ group_bits));
         __builtin_amdgcn_global_load_lds((global_cptr)src, (lds_ptr)(tile + i * 1024), 16, 0, 0);
       }
     } else {
@@ -315,6 +311,14 @@ __global__ void scores_combine(ScoreArgs a, int rows_per_slice, int64_t total_ro
   a.lse[i] = m + (float)log2(s);
 }
 
+// Row normalisers handed over by the caller (natural log, [B, H_q, S_w] per layer) -> log2 domain
+// in the workspace layout, which is the same order: slice (l, b, g), then head within the group, row.
+__global__ void scores_import_lse(ScoreArgs a, const float* const* row_lse, int64_t per_layer, int64_t total) {
+  const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (i >= total) return;
+  a.lse[i] = row_lse[i / per_layer][i % per_layer] * 1.4426950408889634f;
+}
+
 // ------------------------------------------------------------------------------------------
 // Pass 2: normalised weights on the prefix columns; column Mean/Var, entropy, group mean.
 // ------------------------------------------------------------------------------------------
@@ -324,56 +328,75 @@ __device__ __forceinline__ float add_halves(float x) {
   return __uint_as_float(r[0]) + __uint_as_float(r[1]);
 }
 
-template <typename T, int D, int MB>
-__device__ __forceinline__ void pass2_subtile(const char* tile, int sub, int kb, int key_end,
-                                              const typename Frag<T>::type (&qf)[MB][D / Frag<T>::kElems],
-                                              const float (&lse_r)[MB][16], const ScoreArgs& a, float& ent_acc,
-                                              float& var_acc, float* iq_row, int c32, int hh) {
+// One period of pass 2's software pipeline.  The MFMAs of sub-tile `sub` of `tile` accumulate
+// into `dst` while the vector ALU turns the finished logits of the previous sub-tile (`src`,
+// first key kb_prev) into weights and column statistics: after every MFMA step comes the share
+// of that work that keeps both pipes busy, and a scheduling barrier pins the interleaving.
+// src[mb][v]: window row mb*32 + 8*(v/4) + 4*hh + (v%4) of key column kb_prev + c32.
+template <typename T, int D, int MB, bool kMfma, bool kValu>
+__device__ __forceinline__ void pass2_period(const char* tile, int sub,
+                                             const typename Frag<T>::type (&qf)[MB][D / Frag<T>::kElems],
+                                             f32x16 (&dst)[MB], const f32x16 (&src)[MB],
+                                             const float (&lse_r)[MB][16], float cv, int kb_prev, int key_end,
+                                             const ScoreArgs& a, float& ent_acc, float& var_acc, float* iq_row,
+                                             int c32, int hh) {
   using F = Frag<T>;
   using TL = Tile<T, D>;
   constexpr int kSteps = D / F::kElems;
-  f32x16 acc[MB];
-#pragma unroll
-  for (int mb = 0; mb < MB; ++mb)
-#pragma unroll
-    for (int v = 0; v < 16; ++v) acc[mb][v] = 0.f;
-#pragma unroll
-  for (int s = 0; s < kSteps; ++s) {
-    typename F::type kf = F::template load_lds<TL>(tile, sub * 32 + c32, s, hh);
-#pragma unroll
-    for (int mb = 0; mb < MB; ++mb) acc[mb] = F::mfma(qf[mb][s], kf, acc[mb]);
-  }
-  // acc[mb][v]: window row mb*32 + 8*(v/4) + 4*hh + (v%4) of key column kb + c32.
+  constexpr int kGroups = 4 * MB;      // groups of four logits per lane in a sub-tile
+  constexpr int kAhead = 2;            // operand reads in flight ahead of their MFMA step
   // Four independent accumulator sets: consecutive logits do not wait on each other's adds.
   float spv[4] = {0.f, 0.f, 0.f, 0.f}, sp2v[4] = {0.f, 0.f, 0.f, 0.f}, entv[4] = {0.f, 0.f, 0.f, 0.f};
+  typename F::type kf[kSteps];
+  if (kMfma) {
 #pragma unroll
-  for (int mb = 0; mb < MB; ++mb)
+    for (int mb = 0; mb < MB; ++mb)
 #pragma unroll
-    for (int v4 = 0; v4 < 16; v4 += 4) {
-      float t[4], p[4];
+      for (int v = 0; v < 16; ++v) dst[mb][v] = 0.f;
 #pragma unroll
-      for (int i = 0; i < 4; ++i) t[i] = acc[mb][v4 + i] * a.c - lse_r[mb][v4 + i];   // log2 of the weight
+    for (int s = 0; s < kAhead && s < kSteps; ++s) kf[s] = F::template load_lds<TL>(tile, sub * 32 + c32, s, hh);
+  }
 #pragma unroll
-      for (int i = 0; i < 4; ++i) p[i] = fast_exp2(t[i]);
+  for (int s = 0; s < kSteps; ++s) {
+    if (kMfma) {
+      if (s + kAhead < kSteps) kf[s + kAhead] = F::template load_lds<TL>(tile, sub * 32 + c32, s + kAhead, hh);
 #pragma unroll
-      for (int i = 0; i < 4; ++i) {
-        spv[i] += p[i];
-        sp2v[i] = fmaf(p[i], p[i], sp2v[i]);
-        entv[i] = fmaf(p[i], t[i], entv[i]);
+      for (int mb = 0; mb < MB; ++mb) dst[mb] = F::mfma(qf[mb][s], kf[s], dst[mb]);
+    }
+    if (kValu) {
+#pragma unroll
+      for (int gi = 0; gi < kGroups; ++gi) {
+        if (gi * kSteps / kGroups != s) continue;
+        const int mb = gi / 4, v4 = (gi % 4) * 4;
+        float t[4], p[4];
+#pragma unroll
+        for (int i = 0; i < 4; ++i) t[i] = src[mb][v4 + i] * cv - lse_r[mb][v4 + i];   // log2 of the weight
+#pragma unroll
+        for (int i = 0; i < 4; ++i) p[i] = fast_exp2(t[i]);
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+          spv[i] += p[i];
+          sp2v[i] = fmaf(p[i], p[i], sp2v[i]);
+          entv[i] = fmaf(p[i], t[i], entv[i]);
+        }
       }
     }
-  const float ent = (entv[0] + entv[1]) + (entv[2] + entv[3]);
-  const float sp = add_halves((spv[0] + spv[1]) + (spv[2] + spv[3]));
-  const float sp2 = add_halves((sp2v[0] + sp2v[1]) + (sp2v[2] + sp2v[3]));
-  const bool valid = kb + c32 < key_end;
-  const float mean = sp * a.inv_sw;
-  const float var = fmaxf((sp2 - sp * mean) * a.inv_swc, 0.f);
-  if (valid) {
-    ent_acc += ent;
-    if (hh == 0) var_acc += var;
+    __builtin_amdgcn_sched_barrier(0);
   }
-  const float iq = fmaf(a.w_prod * mean, var, fmaf(a.w_var, var, a.w_mean * mean));
-  if (hh == 0) iq_row[sub * 32 + c32] = valid ? iq : 0.f;
+  if (kValu) {
+    const float ent = (entv[0] + entv[1]) + (entv[2] + entv[3]);
+    const float sp = add_halves((spv[0] + spv[1]) + (spv[2] + spv[3]));
+    const float sp2 = add_halves((sp2v[0] + sp2v[1]) + (sp2v[2] + sp2v[3]));
+    const bool valid = kb_prev + c32 < key_end;
+    const float mean = sp * a.inv_sw;
+    const float var = fmaxf((sp2 - sp * mean) * a.inv_swc, 0.f);
+    if (valid) {
+      ent_acc += ent;
+      if (hh == 0) var_acc += var;
+    }
+    const float iq = fmaf(a.w_prod * mean, var, fmaf(a.w_var, var, a.w_mean * mean));
+    if (hh == 0) iq_row[c32] = valid ? iq : 0.f;
+  }
 }
 
 template <typename T, int D, int MB>
@@ -383,7 +406,8 @@ __global__ __launch_bounds__(512) void scores_pass2(ScoreArgs a) {
   constexpr int kSteps = D / F::kElems;
   __shared__ __attribute__((aligned(1024))) char buf0[TL::kBytes];
   __shared__ __attribute__((aligned(1024))) char buf1[TL::kBytes];
-  __shared__ float iq_lds[2][8][kTileKeys];
+  // I_q of the G heads for three tiles in rotation: one being read by the flush, two being written
+  __shared__ float iq_lds[3][8][kTileKeys];
 
   const int chunk_id = blockIdx.x, slice = blockIdx.y;
   int l, b, g;
@@ -411,40 +435,53 @@ __global__ __launch_bounds__(512) void scores_pass2(ScoreArgs a) {
   for (int mb = 0; mb < MB; ++mb)
 #pragma unroll
     for (int v = 0; v < 16; ++v) lse_r[mb][v] = lse[mb * 32 + 8 * (v / 4) + 4 * hh + (v % 4)];
+  float cv = a.c;
+  asm volatile("" : "+v"(cv));     // a vector register: a scalar operand halves the issue rate of the multiply
 
   float ent_acc = 0.f, var_acc = 0.f;
   float* raw = a.raw + (int64_t)slice * a.n_p;
+  f32x16 acc_a[MB], acc_b[MB];     // logits of even / odd sub-tiles
 
-  // Group mean of the G heads' I_q for the 64 keys of tile t, written by the first wave.
+  // Group mean of the G heads' I_q for the 64 keys of tile t; every wave writes its share of the keys.
+  const int flush_per = (kTileKeys + n_waves - 1) / n_waves;
   auto flush = [&](int t) {
-    const int key = key0 + t * kTileKeys + (int)threadIdx.x;
-    if (threadIdx.x < kTileKeys && key < key_end) {
+    const int kl = w * flush_per + lane;                 // key within the tile
+    const int key = key0 + t * kTileKeys + kl;
+    if (lane < flush_per && kl < kTileKeys && key < key_end) {
       float s = 0.f;
-      for (int ww = 0; ww < a.group; ++ww) s += iq_lds[t & 1][ww][threadIdx.x];
+#pragma unroll
+      for (int ww = 0; ww < 8; ++ww) {
+        const float x = iq_lds[t % 3][ww][kl];           // rows >= G are never written and never used
+        s += ww < a.group ? x : 0.f;
+      }
       raw[key] = s * a.inv_g;
     }
   };
+  // Tile t: its first sub-tile's MFMAs run beside the statistics of tile t-1's second sub-tile,
+  // its second sub-tile's MFMAs beside the statistics of its first.
   auto stage = [&](const char* cur, char* nxt, int t) {
     wait_vmem();
-    __syncthreads();       // tile t complete in `cur`; `nxt` and iq_lds[t&1] free; tile t-1's I_q written
+    __syncthreads();       // tile t complete in `cur`; every wave is done with `nxt` and with tile t-2's I_q
     const int t0 = key0 + t * kTileKeys;
     if (t + 1 < n_tiles) mover.issue(nxt, t0 + kTileKeys);
-    if (t > 0) flush(t - 1);
-#pragma unroll
-    for (int sub = 0; sub < kTileKeys / 32; ++sub) {
-      const int kb = t0 + sub * 32;
-      if (kb >= key_end) {           // whole sub-tile beyond the prefix
-        if (hh == 0) iq_lds[t & 1][w][sub * 32 + c32] = 0.f;
-        continue;
-      }
-      pass2_subtile<T, D, MB>(cur, sub, kb, key_end, qf, lse_r, a, ent_acc, var_acc, iq_lds[t & 1][w], c32, hh);
-    }
+    if (t >= 2) flush(t - 2);
+    if (t == 0)
+      pass2_period<T, D, MB, true, false>(cur, 0, qf, acc_a, acc_b, lse_r, cv, 0, key_end, a, ent_acc, var_acc, nullptr, c32, hh);
+    else
+      pass2_period<T, D, MB, true, true>(cur, 0, qf, acc_a, acc_b, lse_r, cv, t0 - 32, key_end, a, ent_acc, var_acc,
+                                         &iq_lds[(t - 1) % 3][w][32], c32, hh);
+    pass2_period<T, D, MB, true, true>(cur, 1, qf, acc_b, acc_a, lse_r, cv, t0, key_end, a, ent_acc, var_acc,
+                                       &iq_lds[t % 3][w][0], c32, hh);
   };
   for (int t = 0; t < n_tiles; t += 2) {
     stage(buf0, buf1, t);
     if (t + 1 < n_tiles) stage(buf1, buf0, t + 1);
   }
+  // drain: statistics of the last sub-tile
+  pass2_period<T, D, MB, false, true>(buf0, 0, qf, acc_a, acc_b, lse_r, cv, key0 + (n_tiles - 1) * kTileKeys + 32, key_end, a,
+                                      ent_acc, var_acc, &iq_lds[(n_tiles - 1) % 3][w][32], c32, hh);
   __syncthreads();
+  if (n_tiles >= 2) flush(n_tiles - 2);
   flush(n_tiles - 1);
 
   // Per-wave sums in a fixed order.
@@ -530,14 +567,21 @@ inline void mark(int i, hipStream_t stream) {
 }
 
 template <typename T, int D, int MB>
-int launch_scores(const ScoreArgs& a, int64_t n_slices, hipStream_t stream) {
+int launch_scores(const ScoreArgs& a, int64_t n_slices, const float* const* row_lse, hipStream_t stream) {
   dim3 block(64 * a.group);
-  mark(0, stream);
-  hipLaunchKernelGGL((scores_pass1<T, D, MB>), dim3(a.n_chunks, (unsigned)n_slices), block, 0, stream, a);
-  mark(1, stream);
   const int rows = a.group * MB * 32;
   const int64_t total_rows = n_slices * rows;
-  hipLaunchKernelGGL(scores_combine, dim3((unsigned)((total_rows + 255) / 256)), dim3(256), 0, stream, a, rows, total_rows);
+  mark(0, stream);
+  if (row_lse == nullptr) {
+    hipLaunchKernelGGL((scores_pass1<T, D, MB>), dim3(a.n_chunks, (unsigned)n_slices), block, 0, stream, a);
+    mark(1, stream);
+    hipLaunchKernelGGL(scores_combine, dim3((unsigned)((total_rows + 255) / 256)), dim3(256), 0, stream, a, rows, total_rows);
+  } else {
+    const int64_t per_layer = (int64_t)a.batch * a.h_kv * rows;
+    hipLaunchKernelGGL(scores_import_lse, dim3((unsigned)((total_rows + 255) / 256)), dim3(256), 0, stream, a, row_lse,
+                       per_layer, total_rows);
+    mark(1, stream);
+  }
   mark(2, stream);
   hipLaunchKernelGGL((scores_pass2<T, D, MB>), dim3(a.n_chunks_p, (unsigned)n_slices), block, 0, stream, a);
   mark(3, stream);
@@ -575,11 +619,12 @@ extern "C" int cake_profile_read(float* ms) {
   return CAKE_OK;
 }
 
-extern "C" int cake_window_scores(const cake_shape* shape, const cake_params* params,
-                                  const void* const* q_win, const void* const* k,
-                                  const int64_t* q_strides, const int64_t* k_strides,
-                                  float* const* indicator,
-                                  void* workspace, size_t workspace_bytes, void* stream) {
+namespace {
+int window_scores_impl(const cake_shape* shape, const cake_params* params,
+                       const void* const* q_win, const void* const* k,
+                       const int64_t* q_strides, const int64_t* k_strides,
+                       const float* const* row_lse, float* const* indicator,
+                       void* workspace, size_t workspace_bytes, void* stream) {
   if (int rc = check_shape_scores(shape)) return rc;
   CAKE_REQUIRE(params != nullptr, "params is NULL");
   CAKE_REQUIRE(q_win && k && indicator, "q_win, k or indicator table is NULL");
@@ -626,7 +671,7 @@ extern "C" int cake_window_scores(const cake_shape* shape, const cake_params* pa
   a.raw = reinterpret_cast<float*>(ws + lay.off_raw);
   hipStream_t st = static_cast<hipStream_t>(stream);
 
-#define CAKE_DISPATCH(T, D, MB) return launch_scores<T, D, MB>(a, lay.n_slices, st)
+#define CAKE_DISPATCH(T, D, MB) return launch_scores<T, D, MB>(a, lay.n_slices, row_lse, st)
   const bool bf = shape->dtype == CAKE_BF16;
   const int d = shape->head_dim, mb = shape->window / 32;
   if (bf && d == 128 && mb == 1) CAKE_DISPATCH(__bf16, 128, 1);
@@ -639,6 +684,26 @@ extern "C" int cake_window_scores(const cake_shape* shape, const cake_params* pa
   if (!bf && d == 64 && mb == 2) CAKE_DISPATCH(float, 64, 2);
 #undef CAKE_DISPATCH
   return fail(CAKE_ERR_UNSUPPORTED, "no score kernel for this shape");
+}
+}  // namespace
+
+extern "C" int cake_window_scores(const cake_shape* shape, const cake_params* params,
+                                  const void* const* q_win, const void* const* k,
+                                  const int64_t* q_strides, const int64_t* k_strides,
+                                  float* const* indicator,
+                                  void* workspace, size_t workspace_bytes, void* stream) {
+  return window_scores_impl(shape, params, q_win, k, q_strides, k_strides, nullptr, indicator, workspace,
+                            workspace_bytes, stream);
+}
+
+extern "C" int cake_window_scores_lse(const cake_shape* shape, const cake_params* params,
+                                      const void* const* q_win, const void* const* k,
+                                      const int64_t* q_strides, const int64_t* k_strides,
+                                      const float* const* row_lse, float* const* indicator,
+                                      void* workspace, size_t workspace_bytes, void* stream) {
+  CAKE_REQUIRE(row_lse != nullptr, "row_lse table is NULL");
+  return window_scores_impl(shape, params, q_win, k, q_strides, k_strides, row_lse, indicator, workspace,
+                            workspace_bytes, stream);
 }
 
 extern "C" int cake_layer_preference(const cake_shape* shape, const cake_params* params,

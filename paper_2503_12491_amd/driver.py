@@ -39,7 +39,9 @@ class EvictionPass:
     """Buffers and call sequence for one prompt's eviction pass on one GPU."""
 
     def __init__(self, q_win: Sequence[torch.Tensor], k: Sequence[torch.Tensor], v: Sequence[torch.Tensor],
-                 total_budget: int, params=None):
+                 total_budget: int, params=None, row_lse: Optional[Sequence[torch.Tensor]] = None):
+        """row_lse: per layer [B, H_q, S_w] f32 log-sum-exp of the window rows, if the prefill attention
+        already produced it; the scores then take one pass over K (cake_window_scores_lse)."""
         self.q_win, self.k, self.v = list(q_win), list(k), list(v)
         q0, k0 = self.q_win[0], self.k[0]
         self.L = len(self.k)
@@ -67,6 +69,11 @@ class EvictionPass:
         self.tbl_k = C.ptr_table(self.k)
         self.tbl_v = C.ptr_table(self.v)
         self.tbl_ind = C.ptr_table([self.indicator[l] for l in range(self.L)])
+        self.row_lse = None if row_lse is None else [t.contiguous() for t in row_lse]
+        if self.row_lse is not None:
+            for t in self.row_lse:
+                assert t.dtype == torch.float32 and tuple(t.shape) == (self.B, self.H_q, self.S_w)
+            self.tbl_lse = C.ptr_table(self.row_lse)
 
         # Output pools.  Row capacity of layer l is cap_l = max_b keep[l, b]; over all layers
         # sum_l cap_l <= B * (B_total - L*S_w), and exactly B_total - L*S_w when B = 1.
@@ -84,8 +91,12 @@ class EvictionPass:
 
     # ------------------------------------------------------------------ the five calls
     def scores(self, stream=None) -> None:
-        C.cake_window_scores(self.shape, self.params, self.tbl_q, self.tbl_k, _strides3(self.q_win[0]),
-                             _strides3(self.k[0]), self.tbl_ind, self.workspace, stream)
+        if self.row_lse is None:
+            C.cake_window_scores(self.shape, self.params, self.tbl_q, self.tbl_k, _strides3(self.q_win[0]),
+                                 _strides3(self.k[0]), self.tbl_ind, self.workspace, stream)
+        else:
+            C.cake_window_scores_lse(self.shape, self.params, self.tbl_q, self.tbl_k, _strides3(self.q_win[0]),
+                                     _strides3(self.k[0]), self.tbl_lse, self.tbl_ind, self.workspace, stream)
         C.cake_layer_preference(self.shape, self.params, self.workspace, self.pref, self.hv, stream)
 
     def preferences_to_host(self):
@@ -190,8 +201,13 @@ class EvictionPass:
         budgets = None
         for m in range(L):
             # ---- admit layer m: indicator and preference
-            C.cake_window_scores(shape1, self.params, self.tbl_q[m:m + 1], self.tbl_k[m:m + 1],
-                                 _strides3(self.q_win[m]), _strides3(self.k[m]), self.tbl_ind[m:m + 1], ws1)
+            if self.row_lse is None:
+                C.cake_window_scores(shape1, self.params, self.tbl_q[m:m + 1], self.tbl_k[m:m + 1],
+                                     _strides3(self.q_win[m]), _strides3(self.k[m]), self.tbl_ind[m:m + 1], ws1)
+            else:
+                C.cake_window_scores_lse(shape1, self.params, self.tbl_q[m:m + 1], self.tbl_k[m:m + 1],
+                                         _strides3(self.q_win[m]), _strides3(self.k[m]), self.tbl_lse[m:m + 1],
+                                         self.tbl_ind[m:m + 1], ws1)
             C.cake_layer_preference(shape1, self.params, ws1, pref1, hv1)
             pref[:, m] = pref1.cpu().numpy()[:, 0]
             hv[:, m] = hv1.cpu().numpy()[:, 0]

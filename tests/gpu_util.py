@@ -36,9 +36,11 @@ def host64(t: torch.Tensor) -> np.ndarray:
     return t.detach().to("cpu").to(torch.float64).numpy()
 
 
-def oracle_layer(q_win_b, k_b, params):
-    """Oracle pass for one (layer, sequence): q_win_b [H_q,S_w,d], k_b [H_kv,N,d] device tensors."""
-    return co.layer_pass(host64(q_win_b), host64(k_b), oracle_params(params))
+def oracle_layer(q_win_b, k_b, params, row_lse_b=None):
+    """Oracle pass for one (layer, sequence): q_win_b [H_q,S_w,d], k_b [H_kv,N,d] device tensors
+    (and, for the hand-off path, the same f32 row normalisers [H_q,S_w] the GPU was given)."""
+    return co.layer_pass(host64(q_win_b), host64(k_b), oracle_params(params),
+                         None if row_lse_b is None else host64(row_lse_b))
 
 
 def oracle_slice(q_win_b, k_b, g, group, params):
@@ -76,3 +78,18 @@ def assert_topk_within_ties(got_idx, oracle_ind_row, k, rtol=RTOL):
         vals = oracle_ind_row[diff]
         assert np.all(np.abs(vals - kth) <= 4 * rtol * abs(kth)), "selection differs away from the k-th cut"
     return int(diff.size)
+
+
+def torch_row_lse(q_win_l: torch.Tensor, k_l: torch.Tensor, scale=None) -> torch.Tensor:
+    """Stand-in for what a prefill attention kernel hands over: ln sum_j exp(scale*<q_r,k_j>) over the
+    keys visible to each window row, computed by torch in fp64 and rounded to f32.  [B, H_q, S_w]."""
+    B, H_q, S_w, d = q_win_l.shape
+    H_kv, N = k_l.shape[1], k_l.shape[2]
+    G = H_q // H_kv
+    scale = scale if scale else d ** -0.5
+    q = q_win_l.double().view(B, H_kv, G, S_w, d)
+    s = torch.einsum("bgwrd,bgnd->bgwrn", q, k_l.double()) * scale
+    pos_q = (N - S_w) + torch.arange(S_w, device=s.device)
+    hidden = torch.arange(N, device=s.device)[None, :] > pos_q[:, None]
+    s = s.masked_fill(hidden, float("-inf"))
+    return torch.logsumexp(s, dim=-1).view(B, H_q, S_w).float().contiguous()

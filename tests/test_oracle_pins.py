@@ -106,6 +106,31 @@ def test_indicator_modes_through_layer_pass():
     np.testing.assert_array_equal(co.layer_pass(q, k, p0)["indicator"], co.layer_pass(q, k, p1)["indicator"])
 
 
+def test_supplied_row_lse_reproduces_the_worked_example_and_scipy():
+    """Window attention from a handed-over log-sum-exp: the rationals of the worked example with
+    lse = ln 6, ln 30 (head 0) and ln 14, ln 10 (head 1); scipy's logsumexp on random inputs; and a
+    shifted lse scales every weight of that row by exp(-shift)."""
+    g, q, k = _example_inputs(["head0", "head1"])
+    lse = np.log(np.array([[6.0, 30.0], [14.0, 10.0]]))
+    a = co.window_attention_given_lse(q, k, lse, scale=1.0)
+    for i, head in enumerate(("head0", "head1")):
+        want = np.array([[_f(x) for x in row] for row in g[head]["a_obs"]])
+        np.testing.assert_allclose(co.observed(a, 2)[i], want, rtol=1e-14)
+    assert a[0, 0, 3] == 0.0                                   # hidden key keeps weight 0
+    rng = np.random.default_rng(7)
+    q = rng.standard_normal((4, 8, 16)) * 2
+    k = rng.standard_normal((2, 60, 16))
+    s = co.window_logits(q, k)
+    lse = scipy.special.logsumexp(s, axis=-1)
+    np.testing.assert_allclose(co.window_attention_given_lse(q, k, lse), co.window_attention(q, k), rtol=1e-12, atol=0)
+    p = co.OracleParams(pool_kernel=3)
+    a1, a2 = co.layer_pass(q, k, p), co.layer_pass(q, k, p, row_lse=lse)
+    np.testing.assert_allclose(a2["indicator"], a1["indicator"], rtol=1e-11)
+    np.testing.assert_allclose([a2["H"], a2["V"], a2["pref"]], [a1["H"], a1["V"], a1["pref"]], rtol=1e-11)
+    shifted = co.window_attention_given_lse(q, k, lse + 0.5)
+    np.testing.assert_allclose(shifted, co.window_attention(q, k) * math.exp(-0.5), rtol=1e-12)
+
+
 # ---------------------------------------------------------------- softmax
 def test_softmax_rows_sum_to_one_and_match_scipy():
     rng = np.random.default_rng(0)

@@ -11,7 +11,8 @@ import torch
 from oracle import cake_oracle as co
 from synth import CONFIGS, make_config_inputs
 
-from gpu_util import (ATOL, RTOL, assert_close, assert_topk_within_ties, host64, load_cake, oracle_layer, say)
+from gpu_util import (ATOL, RTOL, assert_close, assert_topk_within_ties, host64, load_cake, oracle_layer, say,
+                      torch_row_lse)
 
 pytestmark = pytest.mark.gpu
 DEV = "cuda:0"
@@ -127,21 +128,23 @@ def test_select_topk_batched_layers_and_negative_values(cake):
 
 
 # ------------------------------------------------------------------------------------ scores
-def _check_scores(cake, cfg, params=None, layers=None, check_layers=None):
+def _check_scores(cake, cfg, params=None, layers=None, check_layers=None, handoff=False):
     params = params or cake.make_params()
     inp = make_config_inputs(cfg, device=DEV, layers=layers)
     L = len(inp["layers"])
     q = [inp["q_win"][l] for l in range(L)]
     k = [inp["k"][l] for l in range(L)]
     v = [inp["v"][l] for l in range(L)]
-    ev = cake.EvictionPass(q, k, v, cfg.total_budget, params)
+    # handoff: the rows' log-sum-exp comes from outside (here torch), the scores take one pass over K
+    lse = [torch_row_lse(q[l], k[l], params.scale) for l in range(L)] if handoff else None
+    ev = cake.EvictionPass(q, k, v, cfg.total_budget, params, row_lse=lse)
     ev.scores()
     pref, hv = ev.preferences_to_host()
     ind = ev.indicator.cpu().numpy()
     worst = {}
     for l in (check_layers if check_layers is not None else range(L)):
         for b in range(cfg.batch):
-            o = oracle_layer(q[l][b], k[l][b], params)
+            o = oracle_layer(q[l][b], k[l][b], params, lse[l][b] if handoff else None)
             worst["ind"] = max(worst.get("ind", 0), assert_close(ind[l, b], o["indicator"], f"indicator l={l} b={b}"))
             worst["H"] = max(worst.get("H", 0), assert_close(hv[b, l, 0], o["H"], f"H l={l} b={b}"))
             worst["V"] = max(worst.get("V", 0), assert_close(hv[b, l, 1], o["V"], f"V l={l} b={b}"))
@@ -182,6 +185,50 @@ def test_scores_parameter_variants(cake):
     _check_scores(cake, cfg, cake.make_params(gamma=50.0, pool_kernel=3))
     cfg = CONFIGS[2].scaled(n_layers=1, seq_len=1200, head_dim=64, total_budget=512)
     _check_scores(cake, cfg)
+
+
+def test_scores_with_handed_over_row_lse(cake):
+    # single pass over K with the normalisers supplied: against the oracle fed the same f32 values,
+    # and against the library's own two-pass result
+    say("scores with handed-over LSE")
+    for cfg, params in [(CONFIGS[2].scaled(n_layers=2, seq_len=2048 + 32 + 45, total_budget=2 * 400), None),
+                        (CONFIGS[4].scaled(n_layers=1, seq_len=1500, total_budget=300), cake.make_params(scale=0.11, pool_kernel=3)),
+                        (CONFIGS[5].scaled(n_layers=2, batch=2, seq_len=1111, total_budget=2 * 200), None),
+                        (CONFIGS[1], None)]:
+        ev, inp = _check_scores(cake, cfg, params, handoff=True)
+        one_pass = ev.indicator.clone()
+        pref1, hv1 = ev.preferences_to_host()
+        pref1, hv1 = pref1.copy(), hv1.copy()
+        two = cake.EvictionPass(ev.q_win, ev.k, ev.v, cfg.total_budget, ev.params)
+        two.scores()
+        pref2, hv2 = two.preferences_to_host()
+        assert_close(one_pass.cpu().numpy(), two.indicator.cpu().numpy(), "one-pass vs two-pass indicator", rtol=2e-4)
+        assert_close(hv1, hv2, "one-pass vs two-pass H, V", rtol=2e-4)
+        assert_close(pref1, pref2, "one-pass vs two-pass P", rtol=4e-4)
+
+
+def test_pass_with_handed_over_row_lse(cake):
+    say("pass with handed-over LSE")
+    cfg = CONFIGS[2].scaled(n_layers=3, seq_len=3000, total_budget=3 * 500)
+    inp = make_config_inputs(cfg, device=DEV)
+    L = cfg.n_layers
+    q = [inp["q_win"][l] for l in range(L)]
+    k = [inp["k"][l] for l in range(L)]
+    v = [inp["v"][l] for l in range(L)]
+    lse = [torch_row_lse(q[l], k[l]) for l in range(L)]
+    res = cake.EvictionPass(q, k, v, cfg.total_budget, row_lse=lse).run()
+    torch.cuda.synchronize()
+    for b in range(cfg.batch):
+        assert list(res.budgets[:, b]) == co.cascade_allocate(res.pref[b], cfg.total_budget, cfg.window, cfg.seq_len)
+    for l in range(L):
+        o = oracle_layer(q[l][0], k[l][0], cake.make_params(), lse[l][0])
+        n_k = int(res.keep[l, 0])
+        for g in range(cfg.n_kv_heads):
+            got = res.idx[l][0, g, :n_k].cpu().numpy()
+            np.testing.assert_array_equal(got, co.select_topk(res.indicator[l][0, g].double().cpu().numpy(), n_k))
+            assert_topk_within_ties(got, o["indicator"][g], n_k)
+            np.testing.assert_array_equal(res.k_out[l][0, g, : n_k + cfg.window].float().cpu().numpy(),
+                                          co.compact(k[l][0, g].float().cpu().numpy(), got, cfg.window))
 
 
 def test_scores_static_attention_has_no_shift(cake):
