@@ -440,7 +440,11 @@ __global__ __launch_bounds__(512) void scores_pass2(ScoreArgs a) {
 
   float ent_acc = 0.f, var_acc = 0.f;
   float* raw = a.raw + (int64_t)slice * a.n_p;
-  f32x16 acc_a[MB], acc_b[MB];     // logits of even / odd sub-tiles
+  // Two accumulator sets (logits of even / odd sub-tiles) let one sub-tile's MFMAs overlap the
+  // previous one's statistics.  The fp32 kernels hold four times the query fragments and would
+  // spill, so they run the two phases of a sub-tile one after the other on a single set.
+  constexpr bool kPipelined = sizeof(T) == 2;
+  f32x16 acc_a[MB], acc_b[MB];
 
   // Group mean of the G heads' I_q for the 64 keys of tile t; every wave writes its share of the keys.
   const int flush_per = (kTileKeys + n_waves - 1) / n_waves;
@@ -465,20 +469,30 @@ __global__ __launch_bounds__(512) void scores_pass2(ScoreArgs a) {
     const int t0 = key0 + t * kTileKeys;
     if (t + 1 < n_tiles) mover.issue(nxt, t0 + kTileKeys);
     if (t >= 2) flush(t - 2);
-    if (t == 0)
-      pass2_period<T, D, MB, true, false>(cur, 0, qf, acc_a, acc_b, lse_r, cv, 0, key_end, a, ent_acc, var_acc, nullptr, c32, hh);
-    else
-      pass2_period<T, D, MB, true, true>(cur, 0, qf, acc_a, acc_b, lse_r, cv, t0 - 32, key_end, a, ent_acc, var_acc,
-                                         &iq_lds[(t - 1) % 3][w][32], c32, hh);
-    pass2_period<T, D, MB, true, true>(cur, 1, qf, acc_b, acc_a, lse_r, cv, t0, key_end, a, ent_acc, var_acc,
-                                       &iq_lds[t % 3][w][0], c32, hh);
+    if (kPipelined) {
+      if (t == 0)
+        pass2_period<T, D, MB, true, false>(cur, 0, qf, acc_a, acc_b, lse_r, cv, 0, key_end, a, ent_acc, var_acc, nullptr, c32, hh);
+      else
+        pass2_period<T, D, MB, true, true>(cur, 0, qf, acc_a, acc_b, lse_r, cv, t0 - 32, key_end, a, ent_acc, var_acc,
+                                           &iq_lds[(t - 1) % 3][w][32], c32, hh);
+      pass2_period<T, D, MB, true, true>(cur, 1, qf, acc_b, acc_a, lse_r, cv, t0, key_end, a, ent_acc, var_acc,
+                                         &iq_lds[t % 3][w][0], c32, hh);
+    } else {
+#pragma unroll
+      for (int sub = 0; sub < 2; ++sub) {
+        pass2_period<T, D, MB, true, false>(cur, sub, qf, acc_a, acc_a, lse_r, cv, 0, key_end, a, ent_acc, var_acc, nullptr, c32, hh);
+        pass2_period<T, D, MB, false, true>(cur, sub, qf, acc_a, acc_a, lse_r, cv, t0 + sub * 32, key_end, a, ent_acc, var_acc,
+                                            &iq_lds[t % 3][w][sub * 32], c32, hh);
+      }
+    }
   };
   for (int t = 0; t < n_tiles; t += 2) {
     stage(buf0, buf1, t);
     if (t + 1 < n_tiles) stage(buf1, buf0, t + 1);
   }
   // drain: statistics of the last sub-tile
-  pass2_period<T, D, MB, false, true>(buf0, 0, qf, acc_a, acc_b, lse_r, cv, key0 + (n_tiles - 1) * kTileKeys + 32, key_end, a,
+  if (kPipelined)
+    pass2_period<T, D, MB, false, true>(buf0, 0, qf, acc_a, acc_b, lse_r, cv, key0 + (n_tiles - 1) * kTileKeys + 32, key_end, a,
                                       ent_acc, var_acc, &iq_lds[(n_tiles - 1) % 3][w][32], c32, hh);
   __syncthreads();
   if (n_tiles >= 2) flush(n_tiles - 2);

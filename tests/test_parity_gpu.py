@@ -185,6 +185,10 @@ def test_scores_parameter_variants(cake):
     _check_scores(cake, cfg, cake.make_params(gamma=50.0, pool_kernel=3))
     cfg = CONFIGS[2].scaled(n_layers=1, seq_len=1200, head_dim=64, total_budget=512)
     _check_scores(cake, cfg)
+    cfg = CONFIGS[1].scaled(head_dim=128, window=64, seq_len=700)          # fp32, two row blocks per wave
+    _check_scores(cake, cfg)
+    cfg = CONFIGS[1].scaled(window=64, seq_len=450)
+    _check_scores(cake, cfg)
 
 
 def test_scores_with_handed_over_row_lse(cake):
