@@ -113,7 +113,7 @@ def test_select_topk_batched_layers_and_negative_values(cake):
     say("topk batched")
     g = torch.Generator().manual_seed(3)
     L, B, H = 3, 2, 3
-    cur = [[500, 37], [9000, 9000], [64, 1]]
+    cur = [[501, 37], [9003, 9003], [66, 1]]      # row starts fall on all four 16-byte phases
     keep = [[20, 37], [1000, 1], [0, 1]]
     rows = []
     for l in range(L):
