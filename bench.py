@@ -22,10 +22,11 @@ sys.path.insert(0, ROOT)
 HBM_PEAK_GBPS = 8000.0          # MI355X HBM3E
 MFMA_BF16_PEAK_TFLOPS = 2500.0  # dense bf16
 MFMA_F32_PEAK_TFLOPS = 157.3
-VALU_F32_PEAK_TFLOPS = 78.6     # fp32 vector FMA rate without packed instructions (half of 157.3)
-# Vector-ALU issue slots per logit that the arithmetic itself needs (simple op = 1, exp = 2):
-# pass 1: fma, exp, add; pass 2: fma, exp, add, fma, fma.
-VALU_SLOTS_PER_LOGIT = {"scores_pass1": 4, "scores_pass2": 6}
+VALU_F32_PEAK_TFLOPS = 157.3    # published fp32 vector peak: 256 CUs x 4 SIMDs x one 64-lane FMA per 2 cycles x 2.4 GHz
+# Full-rate vector-ALU issue slots per logit that the arithmetic itself needs.  A slot is one
+# wave-wide fp32 instruction at full rate (2 cycles, 64 lanes x 2 flop); v_exp_f32 runs at a quarter
+# of that rate and counts as four.  Pass 1: fma, exp, add = 6; pass 2: fma, exp, add, fma, fma = 8.
+VALU_SLOTS_PER_LOGIT = {"scores_pass1": 6, "scores_pass2": 8}
 
 
 def parse_args():
@@ -224,10 +225,10 @@ def main():
     achieved = alg[dominant] / dom_s / 1e9
     hbm_view = {"achieved": achieved, "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBPS}
     if dominant in VALU_SLOTS_PER_LOGIT:
-        # The score passes are bound by vector-ALU issue, not by HBM (see DESIGN.md, section 6).
-        # One issue slot = one wave-wide fp32 instruction = 64 lanes x 2 flop (an FMA); v_exp_f32
-        # takes two slots.  Peak = 256 CUs x 4 SIMDs x 2.4 GHz / 4 cycles per slot = 78.6 TFLOP/s,
-        # the fp32 vector peak without packed instructions (disabled on this pool).
+        # The score passes are bound by vector-ALU issue, not by HBM (DESIGN.md, section 6).
+        # achieved = logits x slots x 2 flop / time: the flop-equivalents of the minimal
+        # instruction mix (the MFMA work, which shares the SIMD's issue, is not credited; its
+        # rate is in stages.score_mfma_frac).
         logits = tokens_layers * cfg.n_q_heads * cfg.window
         tflops = logits * VALU_SLOTS_PER_LOGIT[dominant] * 2.0 / dom_s / 1e12
         roofline = {"kernel": dominant, "bound": "alu", "achieved": tflops, "peak": VALU_F32_PEAK_TFLOPS,
