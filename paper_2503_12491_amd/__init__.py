@@ -9,4 +9,4 @@ from .binding import (CAKE_BF16, CAKE_F32, CAKE_IND_MEAN, CAKE_IND_MEAN_PLUS_VAR
                       cake_layer_preference, cake_profile_enable, cake_profile_read, cake_select_topk, cake_version, cake_window_scores,  # noqa: F401
                       cake_window_scores_lse,
                       cake_workspace_bytes, make_params, make_shape, ptr_table)
-from .driver import EvictionPass, PassResult  # noqa: F401
+from .driver import CascadeSession, EvictionPass, PassResult  # noqa: F401

@@ -178,79 +178,126 @@ class EvictionPass:
         return self.evict_launch(budgets)
 
     def run_cascade(self, track_positions: bool = True) -> PassResult:
-        """Cascading pass (Sec. 4.2, Alg. 1).  Stage m scores layer m, recomputes B^(m) over the
-        layers seen so far (Eq. 9) and applies EVICT to each of them on its current, already
-        compacted cache and indicator, all affected layers batched into one top-k and one
-        compaction call.  A layer whose budget did not shrink is left as it is (EVICT would keep
-        everything).  With `track_positions` the retained rows' original prefix positions are
-        carried along (index bookkeeping with torch.gather, not part of the method).
-        """
-        L, B, S_w, N_p = self.L, self.B, self.S_w, self.N_p
-        shape1 = C.make_shape(B, 1, self.H_q, self.H_kv, self.d, self.N, S_w, self.dtype)
-        ws1 = torch.empty(C.cake_workspace_bytes(shape1), dtype=torch.uint8, device=self.dev)
-        pref1 = torch.empty(B, 1, dtype=torch.float64, device=self.dev)
-        hv1 = torch.empty(B, 1, 2, dtype=torch.float64, device=self.dev)
-        pref = np.zeros((B, L))
-        hv = np.zeros((B, L, 2))
-        cur_k: List[torch.Tensor] = [None] * L       # current caches [B,H_kv,cap+S_w,d]
-        cur_v: List[torch.Tensor] = [None] * L
-        cur_i: List[torch.Tensor] = [None] * L       # current indicators [B,H_kv,cap]
-        cur_pos: List[Optional[torch.Tensor]] = [None] * L
-        cur_len = np.zeros((L, B), dtype=np.int64)
-        stage_budgets = []
-        budgets = None
-        for m in range(L):
-            # ---- admit layer m: indicator and preference
-            if self.row_lse is None:
-                C.cake_window_scores(shape1, self.params, self.tbl_q[m:m + 1], self.tbl_k[m:m + 1],
-                                     _strides3(self.q_win[m]), _strides3(self.k[m]), self.tbl_ind[m:m + 1], ws1)
-            else:
-                C.cake_window_scores_lse(shape1, self.params, self.tbl_q[m:m + 1], self.tbl_k[m:m + 1],
-                                         _strides3(self.q_win[m]), _strides3(self.k[m]), self.tbl_lse[m:m + 1],
-                                         self.tbl_ind[m:m + 1], ws1)
-            C.cake_layer_preference(shape1, self.params, ws1, pref1, hv1)
-            pref[:, m] = pref1.cpu().numpy()[:, 0]
-            hv[:, m] = hv1.cpu().numpy()[:, 0]
-            cur_k[m], cur_v[m], cur_i[m] = self.k[m], self.v[m], self.indicator[m]
-            cur_len[m, :] = N_p
-            if track_positions:
-                cur_pos[m] = torch.arange(N_p, device=self.dev, dtype=torch.int64).expand(B, self.H_kv, N_p)
-            # ---- B^(m) for the layers seen so far
-            budgets = np.empty((m + 1, B), dtype=np.int64)
-            for b in range(B):
-                budgets[:, b] = C.cake_cascade_allocate(pref[b, : m + 1], self.total_budget, S_w, self.N)
-            stage_budgets.append(budgets.copy())
-            keep = np.minimum(np.maximum(budgets - S_w, 0), cur_len[: m + 1])
-            layers = [l for l in range(m + 1) if np.any(keep[l] < cur_len[l])]
-            if not layers:
-                continue
-            # ---- EVICT the affected layers in one batched call each
-            n = len(layers)
-            shape_n = C.make_shape(B, n, self.H_q, self.H_kv, self.d, self.N, S_w, self.dtype)
-            caps = [int(keep[l].max()) for l in layers]
-            # zero-filled: with a ragged batch the entries past a sequence's own count are never
-            # written by the library, and the position bookkeeping below gathers through them
-            idx = [torch.zeros(B, self.H_kv, max(c, 1), dtype=torch.int32, device=self.dev) for c in caps]
-            k_out = [torch.empty(B, self.H_kv, c + S_w, self.d, dtype=self.dtype, device=self.dev) for c in caps]
-            v_out = [torch.empty_like(t) for t in k_out]
-            i_out = [torch.empty(B, self.H_kv, max(c, 1), dtype=torch.float32, device=self.dev) for c in caps]
-            cl = [int(x) for l in layers for x in cur_len[l]]
-            kk = [int(x) for l in layers for x in keep[l]]
-            t_idx = C.ptr_table(idx)
-            C.cake_select_topk(shape_n, C.ptr_table([cur_i[l] for l in layers]), cl, kk, t_idx)
-            C.cake_compact_kv(shape_n, C.ptr_table([cur_k[l] for l in layers]), C.ptr_table([cur_v[l] for l in layers]),
-                              [_strides3(cur_k[l]) for l in layers], cl, kk, t_idx,
-                              C.ptr_table([cur_i[l] for l in layers]), C.ptr_table(k_out), C.ptr_table(v_out),
-                              C.ptr_table(i_out))
-            for j, l in enumerate(layers):
-                if track_positions:
-                    c = caps[j]
-                    cur_pos[l] = torch.gather(cur_pos[l], 2, idx[j][:, :, :c].long()) if c else cur_pos[l][:, :, :0]
-                cur_k[l], cur_v[l], cur_i[l] = k_out[j], v_out[j], i_out[j]
-                cur_len[l] = keep[l]
-        torch.cuda.synchronize()
-        keep_final = cur_len.copy()
-        idx_final = [p.to(torch.int32) if p is not None else None for p in cur_pos]
-        return PassResult(budgets, keep_final, pref, hv, [self.indicator[l] for l in range(L)], idx_final, cur_k, cur_v,
-                          cur_i, stage_budgets)
+        """Cascading pass (Sec. 4.2, Alg. 1) over the layers this object was built with: every layer
+        is admitted to a CascadeSession in turn.  The full pooled indicators are kept for inspection."""
+        session = CascadeSession(self.L, self.total_budget, self.params, track_positions=track_positions)
+        for m in range(self.L):
+            session.admit(self.q_win[m], self.k[m], self.v[m], None if self.row_lse is None else self.row_lse[m],
+                          indicator_out=self.indicator[m])
+        res = session.result()
+        res.indicator = [self.indicator[l] for l in range(self.L)]
+        return res
 
+
+class CascadeSession:
+    """Alg. 1 as the prefill produces its layers: `admit` takes layer m's window queries, keys and
+    values when the forward pass reaches it, scores the layer, recomputes B^(m) over the layers seen
+    so far (Eq. 9) and applies EVICT to each of them on its current, already compacted cache and
+    indicator, all affected layers batched into one top-k and one compaction call.  A layer whose
+    budget did not shrink is left as it is (EVICT would keep everything).  The session references
+    the caller's K/V of a layer only until that layer's first eviction, so after every stage it
+    holds at most B_total rows per head in all (Sec. 4.2: the prefill's peak stays at the budget
+    plus the layer being admitted).  With `track_positions` the retained rows' original prefix
+    positions are carried along (index bookkeeping with torch.gather, not part of the method)."""
+
+    def __init__(self, n_layers: int, total_budget: int, params=None, track_positions: bool = True):
+        self.L = int(n_layers)
+        self.total_budget = int(total_budget)
+        self.params = params if params is not None else C.make_params()
+        self.track_positions = track_positions
+        self.m = 0                                     # layers admitted so far
+        self.cur_k: List[torch.Tensor] = []            # current caches [B,H_kv,cap+S_w,d]
+        self.cur_v: List[torch.Tensor] = []
+        self.cur_i: List[torch.Tensor] = []            # current indicators [B,H_kv,cap]
+        self.cur_pos: List[Optional[torch.Tensor]] = []
+        self.stage_budgets: list = []
+        self.budgets = None
+        self._geom = None
+
+    def _setup(self, q_win, k):
+        B, H_q, S_w, d = q_win.shape
+        H_kv, N = k.shape[1], k.shape[2]
+        self._geom = (B, H_q, H_kv, S_w, d, N, k.dtype, k.device)
+        self.shape1 = C.make_shape(B, 1, H_q, H_kv, d, N, S_w, k.dtype)
+        self.ws1 = torch.empty(C.cake_workspace_bytes(self.shape1), dtype=torch.uint8, device=k.device)
+        self.pref1 = torch.empty(B, 1, dtype=torch.float64, device=k.device)
+        self.hv1 = torch.empty(B, 1, 2, dtype=torch.float64, device=k.device)
+        self.pref = np.zeros((B, self.L))
+        self.hv = np.zeros((B, self.L, 2))
+        self.cur_len = np.zeros((self.L, B), dtype=np.int64)
+
+    def rows_held(self) -> int:
+        """Cache rows per KV head and sequence that the session holds now (window rows included)."""
+        return int(sum(t.shape[2] for t in self.cur_k))
+
+    def admit(self, q_win: torch.Tensor, k: torch.Tensor, v: torch.Tensor, row_lse: Optional[torch.Tensor] = None,
+              indicator_out: Optional[torch.Tensor] = None) -> np.ndarray:
+        """Stage m = number of layers admitted before this call.  Returns B^(m), shape [m+1, B]."""
+        assert self.m < self.L, "every layer has been admitted"
+        if self._geom is None:
+            self._setup(q_win, k)
+        B, H_q, H_kv, S_w, d, N, dtype, dev = self._geom
+        assert tuple(q_win.shape) == (B, H_q, S_w, d) and tuple(k.shape) == (B, H_kv, N, d) and v.shape == k.shape
+        N_p, m = N - S_w, self.m
+        # ---- admit layer m: indicator and preference
+        ind = indicator_out if indicator_out is not None else torch.empty(B, H_kv, N_p, dtype=torch.float32, device=dev)
+        t_q, t_k, t_i = C.ptr_table([q_win]), C.ptr_table([k]), C.ptr_table([ind])
+        if row_lse is None:
+            C.cake_window_scores(self.shape1, self.params, t_q, t_k, _strides3(q_win), _strides3(k), t_i, self.ws1)
+        else:
+            lse = row_lse.contiguous()
+            C.cake_window_scores_lse(self.shape1, self.params, t_q, t_k, _strides3(q_win), _strides3(k),
+                                     C.ptr_table([lse]), t_i, self.ws1)
+        C.cake_layer_preference(self.shape1, self.params, self.ws1, self.pref1, self.hv1)
+        self.pref[:, m] = self.pref1.cpu().numpy()[:, 0]
+        self.hv[:, m] = self.hv1.cpu().numpy()[:, 0]
+        self.cur_k.append(k); self.cur_v.append(v); self.cur_i.append(ind)
+        self.cur_len[m, :] = N_p
+        self.cur_pos.append(torch.arange(N_p, device=dev, dtype=torch.int64).expand(B, H_kv, N_p)
+                            if self.track_positions else None)
+        self.m = m + 1
+        # ---- B^(m) for the layers seen so far
+        budgets = np.empty((m + 1, B), dtype=np.int64)
+        for b in range(B):
+            budgets[:, b] = C.cake_cascade_allocate(self.pref[b, : m + 1], self.total_budget, S_w, N)
+        self.budgets = budgets
+        self.stage_budgets.append(budgets.copy())
+        keep = np.minimum(np.maximum(budgets - S_w, 0), self.cur_len[: m + 1])
+        layers = [l for l in range(m + 1) if np.any(keep[l] < self.cur_len[l])]
+        if not layers:
+            return budgets
+        # ---- EVICT the affected layers in one batched call each
+        n = len(layers)
+        shape_n = C.make_shape(B, n, H_q, H_kv, d, N, S_w, dtype)
+        caps = [int(keep[l].max()) for l in layers]
+        # zero-filled: with a ragged batch the entries past a sequence's own count are never
+        # written by the library, and the position bookkeeping below gathers through them
+        idx = [torch.zeros(B, H_kv, max(c, 1), dtype=torch.int32, device=dev) for c in caps]
+        k_out = [torch.empty(B, H_kv, c + S_w, d, dtype=dtype, device=dev) for c in caps]
+        v_out = [torch.empty_like(t) for t in k_out]
+        i_out = [torch.empty(B, H_kv, max(c, 1), dtype=torch.float32, device=dev) for c in caps]
+        cl = [int(x) for l in layers for x in self.cur_len[l]]
+        kk = [int(x) for l in layers for x in keep[l]]
+        t_idx = C.ptr_table(idx)
+        t_ind = C.ptr_table([self.cur_i[l] for l in layers])
+        C.cake_select_topk(shape_n, t_ind, cl, kk, t_idx)
+        C.cake_compact_kv(shape_n, C.ptr_table([self.cur_k[l] for l in layers]),
+                          C.ptr_table([self.cur_v[l] for l in layers]),
+                          [_strides3(self.cur_k[l]) for l in layers], cl, kk, t_idx, t_ind, C.ptr_table(k_out),
+                          C.ptr_table(v_out), C.ptr_table(i_out))
+        for j, l in enumerate(layers):
+            if self.track_positions:
+                c = caps[j]
+                self.cur_pos[l] = (torch.gather(self.cur_pos[l], 2, idx[j][:, :, :c].long()) if c
+                                   else self.cur_pos[l][:, :, :0])
+            self.cur_k[l], self.cur_v[l], self.cur_i[l] = k_out[j], v_out[j], i_out[j]
+            self.cur_len[l] = keep[l]
+        return budgets
+
+    def result(self) -> PassResult:
+        """The caches, indicators and (if tracked) original positions after the stages so far."""
+        torch.cuda.synchronize()
+        m = self.m
+        idx_final = [p.to(torch.int32) if p is not None else None for p in self.cur_pos]
+        return PassResult(self.budgets, self.cur_len[:m].copy(), self.pref[:, :m].copy(), self.hv[:, :m].copy(), [],
+                          idx_final, list(self.cur_k), list(self.cur_v), list(self.cur_i), list(self.stage_budgets))

@@ -69,3 +69,52 @@ def test_cascade_equals_one_shot(cake, name):
             for g in range(cfg.n_kv_heads):
                 np.testing.assert_array_equal(casc.idx[l][0, g, :n_k].cpu().numpy(), cache[l]["pos"][g])
                 np.testing.assert_array_equal(casc.k_out[l][0, g, : n_k + S_w].float().cpu().numpy(), cache[l]["k"][g])
+
+
+def test_streaming_session_holds_the_budget_after_every_stage(cake):
+    # layers are generated, admitted and released one at a time, as a prefill would produce them
+    from synth import make_layer
+    cfg = CONFIGS[2].scaled(n_layers=6, seq_len=2048 + 32 + 9, total_budget=6 * 300)
+    say("cascade: streaming session")
+    session = cake.CascadeSession(cfg.n_layers, cfg.total_budget)
+    for l in range(cfg.n_layers):
+        one = make_layer(cfg, l, 0, device=DEV)
+        stage = session.admit(one["q_win"][None], one["k"][None], one["v"][None])
+        del one
+        assert stage.shape == (l + 1, 1) and stage.sum() == min(cfg.total_budget, (l + 1) * cfg.seq_len)
+        assert session.rows_held() == stage.sum()                 # B = 1: exactly the budget, window rows included
+    streamed = session.result()
+    inp = make_config_inputs(cfg, device=DEV)
+    L = cfg.n_layers
+    args = ([inp["q_win"][l] for l in range(L)], [inp["k"][l] for l in range(L)], [inp["v"][l] for l in range(L)])
+    batch = cake.EvictionPass(*args, cfg.total_budget).run_cascade()
+    np.testing.assert_array_equal(streamed.budgets, batch.budgets)
+    np.testing.assert_array_equal(streamed.pref, batch.pref)
+    np.testing.assert_array_equal(streamed.keep, batch.keep)
+    for l in range(L):
+        n_k = int(batch.keep[l, 0])
+        assert torch.equal(streamed.k_out[l], batch.k_out[l]) and torch.equal(streamed.v_out[l], batch.v_out[l])
+        assert torch.equal(streamed.idx[l][..., :n_k], batch.idx[l][..., :n_k])
+        assert torch.equal(streamed.ind_out[l][..., :n_k], batch.ind_out[l][..., :n_k])
+
+
+def test_cascade_with_handed_over_row_lse_equals_one_shot(cake):
+    from gpu_util import torch_row_lse
+    cfg = CONFIGS[2].scaled(n_layers=4, seq_len=1500, total_budget=4 * 250)
+    say("cascade with handed-over LSE")
+    inp = make_config_inputs(cfg, device=DEV)
+    L = cfg.n_layers
+    q = [inp["q_win"][l] for l in range(L)]
+    k = [inp["k"][l] for l in range(L)]
+    v = [inp["v"][l] for l in range(L)]
+    lse = [torch_row_lse(q[l], k[l]) for l in range(L)]
+    shot = cake.EvictionPass(q, k, v, cfg.total_budget, row_lse=lse).run()
+    torch.cuda.synchronize()
+    shot_k = [t.clone() for t in shot.k_out]
+    shot_idx = [t.clone() for t in shot.idx]
+    casc = cake.EvictionPass(q, k, v, cfg.total_budget, row_lse=lse).run_cascade()
+    np.testing.assert_array_equal(casc.budgets, shot.budgets)
+    for l in range(L):
+        n_k = int(shot.keep[l, 0])
+        assert torch.equal(casc.idx[l][0, :, :n_k], shot_idx[l][0, :, :n_k])
+        assert torch.equal(casc.k_out[l][0, :, : n_k + cfg.window], shot_k[l][0, :, : n_k + cfg.window])
