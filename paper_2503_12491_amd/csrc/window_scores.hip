@@ -15,6 +15,8 @@
 //           ONE key column and the Mean/Var over the S_w rows are in-register sums); weights
 //           p = exp2(t), t = logit*scale*log2(e) - lse2; per column sum p, sum p^2; entropy
 //           sum p*t; group mean of I_q through LDS                      -> un-pooled indicator
+//           (software-pipelined for bf16: the MFMAs of one 32-key sub-tile are interleaved with
+//           the statistics of the previous one)
 //   pool    stride-1 max-pool over prefix positions                              -> indicator
 //   pref    fixed-order fp64 reduction of the per-chunk entropy/variance sums    -> P_l, H_l, V_l
 //
@@ -23,6 +25,8 @@
 // bytes per lane), double-buffered so that tile t+1 is in flight while tile t is consumed, and
 // are shared by the G waves.  Rows are stored unpadded with their 16-byte pieces XOR-swizzled by
 // the row index so that the MFMA operand reads spread over the banks.
+// With the row normalisers supplied by the caller (cake_window_scores_lse) pass 1 and the
+// combine give way to a kernel that converts them to the log2 domain.
 // Everything is deterministic: no float atomics, fixed reduction orders.
 #include <cmath>
 
