@@ -90,8 +90,8 @@ int cake_version(void);
 /* Reason for the calling thread's most recent failure; "" if none. */
 const char* cake_last_error(void);
 
-/* Bytes of device workspace that cake_window_scores(_lse), cake_layer_preference and
- * cake_select_topk need for `shape` (the maximum over the three).  The workspace must be
+/* Bytes of device workspace that cake_window_scores(_lse), cake_layer_preference,
+ * cake_decode_update and cake_select_topk need for `shape` (the maximum over them).  The workspace must be
  * 256-byte aligned.  cake_layer_preference reads what cake_window_scores left in it, so the
  * same buffer must be passed to both with nothing else written in between. */
 int cake_workspace_bytes(const cake_shape* shape, size_t* bytes /* host, out */);
@@ -208,6 +208,35 @@ int cake_compact_kv(const cake_shape* shape,
                     const float* const* ind_in,
                     void* const* k_out, void* const* v_out, float* const* ind_out,
                     void* stream);
+
+/*
+ * Indicator maintenance for one generated token (implementation appendix, decoding branch of
+ * the listing: the new query's attention over the cached keys outside the window is pooled and
+ * the stored indicator is updated with it; "tokens are evicted during both prefilling and
+ * decoding", Sec. 5 implementation details).  The paper does not define the update; this
+ * library ADDS the pooled weights to the stored values.
+ *
+ * Sequence b of layer l holds cur_len scored rows followed by its S_w window rows, the last of
+ * which is the new token's key (the row that just left the window is the last scored row and
+ * enters with whatever indicator the caller stored for it, normally 0).  For every KV head the G
+ * query heads' new rows attend to all cur_len + S_w rows (softmax over all of them); the weights
+ * on the scored rows are averaged over the group, max-pooled with params.pool_kernel along the
+ * row axis (edges clipped) and added to indicator[l][b, g, :cur_len].  Only the mean term of
+ * Eq. 11 exists for a single query row: gamma and indicator_mode are not used.
+ * Evicting back to the budget is cake_select_topk + cake_compact_kv with k = cur_len - 1.
+ *
+ *   shape      seq_len = row capacity of the caches (>= max cur_len + S_w); n_layers as usual
+ *   q_new      table; q_new[l] -> [B, H_q, d], element strides q_strides (host [2]: batch, head)
+ *   k_cache    table; k_cache[l] -> [B, H_kv, rows, d], element strides k_strides (host [n_layers][3])
+ *   cur_len    host [n_layers*B]: scored rows per (layer, sequence), <= seq_len - S_w
+ *   indicator  table; indicator[l] -> [B, H_kv, max_b cur_len] f32, updated in place
+ *   workspace  device scratch of at least cake_workspace_bytes(shape)
+ */
+int cake_decode_update(const cake_shape* shape, const cake_params* params,
+                       const void* const* q_new, const int64_t* q_strides,
+                       const void* const* k_cache, const int64_t* k_strides,
+                       const int32_t* cur_len, float* const* indicator,
+                       void* workspace, size_t workspace_bytes, void* stream);
 
 /*
  * Diagnostics, not part of the method: per-kernel timing of cake_window_scores.

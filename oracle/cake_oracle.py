@@ -24,7 +24,10 @@ Readings taken where the paper is silent (each also listed in the design notes):
     k_l = B_l - S_w prefix tokens are selected;
   * real-valued budgets of Eq. (7)/(9) become integers by Webster (Sainte-Lague)
     divisor apportionment with a floor of S_w and a cap of N per layer;
-  * top-k breaks ties towards the lower position and returns ascending positions.
+  * top-k breaks ties towards the lower position and returns ascending positions;
+  * in the decoding phase the pooled attention row of the new token is added to the stored
+    indicator (the paper names `update_score` without defining it) and the row that leaves the
+    window starts from 0.
 
 Pins (tests/test_oracle_pins.py): a hand-derived rational worked example,
 closed forms for uniform attention, zero temporal variance under static
@@ -298,3 +301,48 @@ def cascade_manage(prefs, indicators, ks, vs, total_budget: int, window: int):
                 k_hat, v_hat, i_hat, idx = evict(c["k"][g], c["v"][g], c["ind"][g], budgets[l], window)
                 c["k"][g], c["v"][g], c["ind"][g], c["pos"][g] = k_hat, v_hat, i_hat, c["pos"][g][idx]
     return history, cache
+
+
+# ----------------------------------------------------------------------------------------
+# Decode-phase maintenance (implementation appendix, decoding branch of the listing)
+# ----------------------------------------------------------------------------------------
+def decode_update(q_new: np.ndarray, k_rows: np.ndarray, indicator: np.ndarray, window: int, p: OracleParams
+                  ) -> np.ndarray:
+    """One generated token: q_new [H_q, d] attends to all cached rows k_rows [H_kv, n, d] (the last
+    `window` of them are the window, the newest row last); softmax over all n rows per head; the
+    weights on the n - window scored rows are averaged over each KV group, max-pooled, and ADDED to
+    the stored indicator [H_kv, n - window].  Reading: the paper names the update (`update_score`)
+    without defining it; a single query row has a mean but no variance, so gamma plays no part."""
+    q_new = np.asarray(q_new, dtype=np.float64)
+    k_rows = np.asarray(k_rows, dtype=np.float64)
+    h_q, d = q_new.shape
+    h_kv, n, _ = k_rows.shape
+    group = h_q // h_kv
+    scale = p.scale if p.scale is not None else 1.0 / math.sqrt(d)
+    s = np.empty((h_q, n))
+    for h in range(h_q):
+        s[h] = (k_rows[h // group] @ q_new[h]) * scale
+    a = softmax_rows(s)                                  # the new token sees every cached row
+    obs = a[:, : n - window]
+    per_kv = obs.reshape(h_kv, group, n - window).sum(axis=1) / group
+    return np.asarray(indicator, dtype=np.float64) + max_pool(per_kv, p.pool_kernel)
+
+
+def decode_step(q_new, cache: dict, k_new, v_new, window: int, p: OracleParams) -> dict:
+    """Append the new token, update the indicator (decode_update) and evict one scored row per
+    head so that the cache returns to its size (EVICT at k = cur, Eq. 12).  cache = {"k", "v":
+    [H_kv, cur + window, d], "ind": [H_kv, cur]}; the row that leaves the window enters the scored
+    part with indicator 0."""
+    k = np.concatenate([cache["k"], np.asarray(k_new, dtype=np.float64)[:, None, :]], axis=1)
+    v = np.concatenate([cache["v"], np.asarray(v_new, dtype=np.float64)[:, None, :]], axis=1)
+    h_kv, cur = cache["ind"].shape
+    ind = np.concatenate([cache["ind"], np.zeros((h_kv, 1))], axis=1)
+    ind = decode_update(q_new, k, ind, window, p)
+    out = {"k": [], "v": [], "ind": [], "idx": []}
+    for g in range(h_kv):
+        sel = select_topk(ind[g], cur)
+        out["idx"].append(sel)
+        out["k"].append(compact(k[g], sel, window))
+        out["v"].append(compact(v[g], sel, window))
+        out["ind"].append(ind[g][sel])
+    return {"k": np.stack(out["k"]), "v": np.stack(out["v"]), "ind": np.stack(out["ind"]), "idx": np.stack(out["idx"])}

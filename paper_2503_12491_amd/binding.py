@@ -110,6 +110,14 @@ def cake_select_topk(shape, indicator, cur_len, k, idx, workspace=None, stream=N
                                    _ptr(workspace), ws_bytes, _stream(stream)))
 
 
+def cake_decode_update(shape, params, q_new, q_strides, k_cache, k_strides, cur_len, indicator, workspace,
+                       stream=None) -> None:
+    flat = [s for layer in k_strides for s in layer]
+    _check(load().cake_decode_update(ctypes.byref(shape), ctypes.byref(params), _ptr(q_new), _i64(q_strides),
+                                     _ptr(k_cache), _i64(flat), _i32(cur_len), _ptr(indicator), _ptr(workspace),
+                                     workspace.numel() * workspace.element_size(), _stream(stream)))
+
+
 def cake_compact_kv(shape, k_in, v_in, kv_strides, cur_len, k, idx, ind_in, k_out, v_out, ind_out,
                     stream=None) -> None:
     flat = [s for layer in kv_strides for s in layer]

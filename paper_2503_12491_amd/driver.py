@@ -301,3 +301,68 @@ class CascadeSession:
         idx_final = [p.to(torch.int32) if p is not None else None for p in self.cur_pos]
         return PassResult(self.budgets, self.cur_len[:m].copy(), self.pref[:, :m].copy(), self.hv[:, :m].copy(), [],
                           idx_final, list(self.cur_k), list(self.cur_v), list(self.cur_i), list(self.stage_budgets))
+
+
+class DecodeCache:
+    """The evicted caches of a prompt during generation (implementation appendix, decoding branch):
+    every layer stays at the budget the prefill pass gave it.  `step(layer, q_new, k_new, v_new)`
+    appends the token's key and value, lets cake_decode_update fold the new query's pooled
+    attention into the stored indicator and evicts one scored row per head with the library's
+    top-k and compaction (k = cur_len), so the layer returns to its size.  Buffer handling
+    (appending a row, the zero for the row that leaves the window) is plain torch."""
+
+    def __init__(self, result: PassResult, n_q_heads: int, window: int, params=None):
+        self.params = params if params is not None else C.make_params()
+        self.S_w, self.H_q = int(window), int(n_q_heads)
+        self.k = [t for t in result.k_out]                 # [B, H_kv, cap_l + S_w, d]
+        self.v = [t for t in result.v_out]
+        self.cur_len = np.asarray(result.keep, dtype=np.int64).copy()          # [L, B]
+        self.L, self.B = self.cur_len.shape
+        self.ind = []
+        for l in range(self.L):
+            cap = int(self.cur_len[l].max())
+            self.ind.append(result.ind_out[l][:, :, :cap].contiguous() if cap else
+                            result.ind_out[l][:, :, :0].contiguous())
+        self._ws = {}
+
+    def step(self, layer: int, q_new: torch.Tensor, k_new: torch.Tensor, v_new: torch.Tensor) -> None:
+        """q_new [B, H_q, d]; k_new, v_new [B, H_kv, d]: the generated token's projections at `layer`."""
+        l, S_w, B = layer, self.S_w, self.B
+        k_old, v_old, i_old = self.k[l], self.v[l], self.ind[l]
+        H_kv, d = k_old.shape[1], k_old.shape[3]
+        cur = self.cur_len[l]
+        cap = int(cur.max())
+        # ---- append: one more row per sequence; the row that leaves the window starts at 0
+        k_in = torch.empty(B, H_kv, cap + S_w + 1, d, dtype=k_old.dtype, device=k_old.device)
+        v_in = torch.empty_like(k_in)
+        i_in = torch.zeros(B, H_kv, cap + 1, dtype=torch.float32, device=k_old.device)
+        k_in[:, :, : cap + S_w] = k_old[:, :, : cap + S_w]
+        v_in[:, :, : cap + S_w] = v_old[:, :, : cap + S_w]
+        i_in[:, :, :cap] = i_old[:, :, :cap]
+        for b in range(B):
+            n_b = int(cur[b]) + S_w
+            k_in[b, :, n_b] = k_new[b]
+            v_in[b, :, n_b] = v_new[b]
+            i_in[b, :, int(cur[b])] = 0.0
+        cur1 = [int(c) + 1 for c in cur]
+        shape = C.make_shape(B, 1, self.H_q, H_kv, d, cap + S_w + 1, S_w, k_old.dtype)
+        key = (B, H_kv, d, cap, str(k_old.dtype))
+        if key not in self._ws:
+            self._ws = {key: torch.empty(C.cake_workspace_bytes(shape), dtype=torch.uint8, device=k_old.device)}
+        ws = self._ws[key]
+        q_new = q_new.contiguous()
+        t_i = C.ptr_table([i_in])
+        C.cake_decode_update(shape, self.params, C.ptr_table([q_new]), [q_new.stride(0), q_new.stride(1)],
+                             C.ptr_table([k_in]), [_strides3(k_in)], cur1, t_i, ws)
+        # ---- evict one scored row per head: back to cur rows
+        keep = [int(c) for c in cur]
+        idx = torch.zeros(B, H_kv, max(cap, 1), dtype=torch.int32, device=k_old.device)
+        k_out = torch.empty(B, H_kv, cap + S_w, d, dtype=k_old.dtype, device=k_old.device)
+        v_out = torch.empty_like(k_out)
+        i_out = torch.empty(B, H_kv, max(cap, 1), dtype=torch.float32, device=k_old.device)
+        t_idx = C.ptr_table([idx])
+        C.cake_select_topk(shape, t_i, cur1, keep, t_idx)
+        C.cake_compact_kv(shape, C.ptr_table([k_in]), C.ptr_table([v_in]), [_strides3(k_in)], cur1, keep, t_idx, t_i,
+                          C.ptr_table([k_out]), C.ptr_table([v_out]), C.ptr_table([i_out]))
+        self.k[l], self.v[l], self.ind[l] = k_out, v_out, i_out[:, :, :cap]
+        self.last_idx = idx

@@ -423,3 +423,46 @@ def test_cascade_equals_one_shot_many_layers_with_ties():
         for g in range(h_kv):
             np.testing.assert_array_equal(cache[l]["pos"][g], shot[l]["pos"][g])
             np.testing.assert_array_equal(cache[l]["k"][g], shot[l]["k"][g])
+
+
+# ---------------------------------------------------------------- decode-phase maintenance
+def test_decode_update_uniform_and_scipy():
+    """q = 0 gives weight 1/n to every cached row: the indicator grows by exactly 1/n everywhere.
+    Random inputs: scipy's softmax, numpy's group mean and torch's max-pool written out independently."""
+    rng = np.random.default_rng(21)
+    h_q, h_kv, d, n, w = 4, 2, 8, 50, 6
+    k = rng.standard_normal((h_kv, n, d))
+    ind = rng.random((h_kv, n - w))
+    p = co.OracleParams(pool_kernel=3)
+    np.testing.assert_allclose(co.decode_update(np.zeros((h_q, d)), k, ind, w, p), ind + 1.0 / n, rtol=1e-13)
+    q = rng.standard_normal((h_q, d)) * 2
+    got = co.decode_update(q, k, ind, w, p)
+    logits = np.stack([k[h // 2] @ q[h] for h in range(h_q)]) / math.sqrt(d)
+    a = scipy.special.softmax(logits, axis=-1)[:, : n - w]
+    per_kv = np.stack([a[0:2].mean(0), a[2:4].mean(0)])
+    pooled = torch.nn.functional.max_pool1d(torch.from_numpy(per_kv)[None], 3, 1, 1)[0].numpy()
+    np.testing.assert_allclose(got, ind + pooled, rtol=1e-12)
+    # the weights the new token gives to the window rows are not observed: they only take mass away
+    assert np.all(got - ind <= 1.0) and (got - ind).sum() < h_kv * 3.0
+
+
+def test_decode_step_keeps_the_size_and_evicts_the_lowest():
+    rng = np.random.default_rng(22)
+    h_q, h_kv, d, cur, w = 2, 1, 4, 10, 3
+    cache = {"k": rng.standard_normal((h_kv, cur + w, d)), "v": rng.standard_normal((h_kv, cur + w, d)),
+             "ind": np.linspace(0.1, 0.2, cur)[None, :].copy()}
+    p = co.OracleParams(pool_kernel=1)
+    k_new, v_new = rng.standard_normal((h_kv, d)), rng.standard_normal((h_kv, d))
+    out = co.decode_step(np.zeros((h_q, d)), cache, k_new, v_new, w, p)
+    assert out["k"].shape == cache["k"].shape and out["ind"].shape == cache["ind"].shape
+    # uniform attention adds the same amount everywhere, so the row that just left the window
+    # (stored indicator 0) is the one that goes; every older scored row stays in place
+    np.testing.assert_array_equal(out["idx"][0], np.arange(cur))
+    np.testing.assert_array_equal(out["k"][0, :cur], cache["k"][0, :cur])
+    np.testing.assert_array_equal(out["k"][0, cur:], np.concatenate([cache["k"][0, cur + 1:], k_new], axis=0))
+    np.testing.assert_allclose(out["ind"][0], cache["ind"][0] + 1.0 / (cur + w + 1), rtol=1e-13)
+    # a strong attention to the leaving row keeps it and evicts the weakest old row instead
+    cache["k"][0, cur] *= 4.0 / np.linalg.norm(cache["k"][0, cur])          # the longest key by far ...
+    q = np.zeros((h_q, d)); q[:] = 10.0 * cache["k"][0, cur]                  # ... and the query points at it
+    out = co.decode_step(q, cache, k_new, v_new, w, p)
+    assert cur in out["idx"][0] and 0 not in out["idx"][0]
