@@ -45,6 +45,15 @@ constexpr float kMasked = -1.0e30f;  // stands for -inf without producing NaN in
 
 __device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }  // v_exp_f32
 
+// x*c - ref as one v_fma_f32 with this operand order (the accumulator value first, the constant
+// second, all three in vector registers): measured the fastest-issuing form of the instruction;
+// a scalar-register operand or the constant in the first slot lowers the issue rate.
+__device__ __forceinline__ float scale_minus(float x, float c, float ref) {
+  float t;
+  asm("v_fma_f32 %0, %1, %2, -%3" : "=v"(t) : "v"(x), "v"(c), "v"(ref));
+  return t;
+}
+
 template <typename T, int D>
 struct Tile {
   static constexpr int kRowBytes = D * (int)sizeof(T);
@@ -374,7 +383,7 @@ __device__ __forceinline__ void pass2_period(const char* tile, int sub,
         const int mb = gi / 4, v4 = (gi % 4) * 4;
         float t[4], p[4];
 #pragma unroll
-        for (int i = 0; i < 4; ++i) t[i] = src[mb][v4 + i] * cv - lse_r[mb][v4 + i];   // log2 of the weight
+        for (int i = 0; i < 4; ++i) t[i] = scale_minus(src[mb][v4 + i], cv, lse_r[mb][v4 + i]);   // log2 of the weight
 #pragma unroll
         for (int i = 0; i < 4; ++i) p[i] = fast_exp2(t[i]);
 #pragma unroll
