@@ -15,8 +15,8 @@
 //           ONE key column and the Mean/Var over the S_w rows are in-register sums); weights
 //           p = exp2(t), t = logit*scale*log2(e) - lse2; per column sum p, sum p^2; entropy
 //           sum p*t; group mean of I_q through LDS                      -> un-pooled indicator
-//           (software-pipelined for bf16: the MFMAs of one 32-key sub-tile are interleaved with
-//           the statistics of the previous one)
+//           (software-pipelined for bf16 at S_w = 64: the MFMAs of one 32-key sub-tile are
+//           interleaved with the statistics of the previous one)
 //   pool    stride-1 max-pool over prefix positions                              -> indicator
 //   pref    fixed-order fp64 reduction of the per-chunk entropy/variance sums    -> P_l, H_l, V_l
 //
@@ -48,6 +48,9 @@ __device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_ex
 // x*c - ref as one v_fma_f32 with this operand order (the accumulator value first, the constant
 // second, all three in vector registers): measured the fastest-issuing form of the instruction;
 // a scalar-register operand or the constant in the first slot lowers the issue rate.
+// The compiler does not see through the statement: it inserts none of the wait states an
+// MFMA result needs before a vector instruction may read it.  Use it only on accumulators whose
+// MFMAs were issued at least a whole sub-tile of instructions earlier.
 __device__ __forceinline__ float scale_minus(float x, float c, float ref) {
   float t;
   asm("v_fma_f32 %0, %1, %2, -%3" : "=v"(t) : "v"(x), "v"(c), "v"(ref));
@@ -346,7 +349,9 @@ __device__ __forceinline__ float add_halves(float x) {
 // first key kb_prev) into weights and column statistics: after every MFMA step comes the share
 // of that work that keeps both pipes busy, and a scheduling barrier pins the interleaving.
 // src[mb][v]: window row mb*32 + 8*(v/4) + 4*hh + (v%4) of key column kb_prev + c32.
-template <typename T, int D, int MB, bool kMfma, bool kValu>
+// kSettled: `src` was written by MFMAs of an earlier period (software pipeline), not by the
+// call just before this one.
+template <typename T, int D, int MB, bool kMfma, bool kValu, bool kSettled>
 __device__ __forceinline__ void pass2_period(const char* tile, int sub,
                                              const typename Frag<T>::type (&qf)[MB][D / Frag<T>::kElems],
                                              f32x16 (&dst)[MB], const f32x16 (&src)[MB],
@@ -383,7 +388,8 @@ __device__ __forceinline__ void pass2_period(const char* tile, int sub,
         const int mb = gi / 4, v4 = (gi % 4) * 4;
         float t[4], p[4];
 #pragma unroll
-        for (int i = 0; i < 4; ++i) t[i] = scale_minus(src[mb][v4 + i], cv, lse_r[mb][v4 + i]);   // log2 of the weight
+        for (int i = 0; i < 4; ++i)                                             // log2 of the weight
+          t[i] = kSettled ? scale_minus(src[mb][v4 + i], cv, lse_r[mb][v4 + i]) : src[mb][v4 + i] * cv - lse_r[mb][v4 + i];
 #pragma unroll
         for (int i = 0; i < 4; ++i) p[i] = fast_exp2(t[i]);
 #pragma unroll
@@ -454,9 +460,11 @@ __global__ __launch_bounds__(512) void scores_pass2(ScoreArgs a) {
   float ent_acc = 0.f, var_acc = 0.f;
   float* raw = a.raw + (int64_t)slice * a.n_p;
   // Two accumulator sets (logits of even / odd sub-tiles) let one sub-tile's MFMAs overlap the
-  // previous one's statistics.  The fp32 kernels hold four times the query fragments and would
-  // spill, so they run the two phases of a sub-tile one after the other on a single set.
-  constexpr bool kPipelined = sizeof(T) == 2;
+  // previous one's statistics.  Measured, this pays for bf16 with two row blocks per wave
+  // (S_w = 64); with one row block the periods are too short and the plain order is faster, and
+  // the fp32 kernels hold four times the query fragments and would spill.  Those run the two
+  // phases of a sub-tile one after the other on a single set.
+  constexpr bool kPipelined = sizeof(T) == 2 && MB == 2;
   f32x16 acc_a[MB], acc_b[MB];
 
   // Group mean of the G heads' I_q for the 64 keys of tile t; every wave writes its share of the keys.
@@ -483,18 +491,24 @@ __global__ __launch_bounds__(512) void scores_pass2(ScoreArgs a) {
     if (t + 1 < n_tiles) mover.issue(nxt, t0 + kTileKeys);
     if (t >= 2) flush(t - 2);
     if (kPipelined) {
-      if (t == 0)
-        pass2_period<T, D, MB, true, false>(cur, 0, qf, acc_a, acc_b, lse_r, cv, 0, key_end, a, ent_acc, var_acc, nullptr, c32, hh);
-      else
-        pass2_period<T, D, MB, true, true>(cur, 0, qf, acc_a, acc_b, lse_r, cv, t0 - 32, key_end, a, ent_acc, var_acc,
-                                           &iq_lds[(t - 1) % 3][w][32], c32, hh);
-      pass2_period<T, D, MB, true, true>(cur, 1, qf, acc_b, acc_a, lse_r, cv, t0, key_end, a, ent_acc, var_acc,
-                                         &iq_lds[t % 3][w][0], c32, hh);
+      if (t == 0) {
+        // the first sub-tile has nothing to run beside; the second one reads its logits straight
+        // after its MFMAs (not settled: the compiler places the wait)
+        pass2_period<T, D, MB, true, false, false>(cur, 0, qf, acc_a, acc_b, lse_r, cv, 0, key_end, a, ent_acc, var_acc, nullptr,
+                                                   c32, hh);
+        pass2_period<T, D, MB, true, true, false>(cur, 1, qf, acc_b, acc_a, lse_r, cv, t0, key_end, a, ent_acc, var_acc,
+                                                  &iq_lds[t % 3][w][0], c32, hh);
+      } else {
+        pass2_period<T, D, MB, true, true, true>(cur, 0, qf, acc_a, acc_b, lse_r, cv, t0 - 32, key_end, a, ent_acc, var_acc,
+                                                 &iq_lds[(t - 1) % 3][w][32], c32, hh);
+        pass2_period<T, D, MB, true, true, true>(cur, 1, qf, acc_b, acc_a, lse_r, cv, t0, key_end, a, ent_acc, var_acc,
+                                                 &iq_lds[t % 3][w][0], c32, hh);
+      }
     } else {
 #pragma unroll
       for (int sub = 0; sub < 2; ++sub) {
-        pass2_period<T, D, MB, true, false>(cur, sub, qf, acc_a, acc_a, lse_r, cv, 0, key_end, a, ent_acc, var_acc, nullptr, c32, hh);
-        pass2_period<T, D, MB, false, true>(cur, sub, qf, acc_a, acc_a, lse_r, cv, t0 + sub * 32, key_end, a, ent_acc, var_acc,
+        pass2_period<T, D, MB, true, false, false>(cur, sub, qf, acc_a, acc_a, lse_r, cv, 0, key_end, a, ent_acc, var_acc, nullptr, c32, hh);
+        pass2_period<T, D, MB, false, true, false>(cur, sub, qf, acc_a, acc_a, lse_r, cv, t0 + sub * 32, key_end, a, ent_acc, var_acc,
                                             &iq_lds[t % 3][w][sub * 32], c32, hh);
       }
     }
@@ -505,7 +519,7 @@ __global__ __launch_bounds__(512) void scores_pass2(ScoreArgs a) {
   }
   // drain: statistics of the last sub-tile
   if (kPipelined)
-    pass2_period<T, D, MB, false, true>(buf0, 0, qf, acc_a, acc_b, lse_r, cv, key0 + (n_tiles - 1) * kTileKeys + 32, key_end, a,
+    pass2_period<T, D, MB, false, true, true>(buf0, 0, qf, acc_a, acc_b, lse_r, cv, key0 + (n_tiles - 1) * kTileKeys + 32, key_end, a,
                                       ent_acc, var_acc, &iq_lds[(n_tiles - 1) % 3][w][32], c32, hh);
   __syncthreads();
   if (n_tiles >= 2) flush(n_tiles - 2);
