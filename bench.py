@@ -225,7 +225,8 @@ def main():
     achieved = alg[dominant] / dom_s / 1e9
     hbm_view = {"achieved": achieved, "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBPS}
     if dominant in VALU_SLOTS_PER_LOGIT:
-        # The score passes are bound by vector-ALU issue, not by HBM.
+        # The score passes are bound by vector-ALU issue, not by HBM: per key they need G*S_w
+        # exponentials and 3-4 more vector instructions per logit next to the MFMAs.
         # achieved = logits x slots x 2 flop / time: the flop-equivalents of the minimal
         # instruction mix (the MFMA work, which shares the SIMD's issue, is not credited; its
         # rate is in stages.score_mfma_frac).
