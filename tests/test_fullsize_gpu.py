@@ -7,7 +7,7 @@ import pytest
 import torch
 
 from oracle import cake_oracle as co
-from synth import CONFIGS, make_layer
+from synth import CONFIGS, make_config_inputs, make_layer
 
 from gpu_util import assert_close, assert_topk_within_ties, load_cake, oracle_layer, oracle_slice, say
 
@@ -104,3 +104,26 @@ def test_config4_llama_128k_bench_configuration(cake):
 def test_config5_gqa5_batch4(cake):
     say("full size: config 5")
     _check_sampled(cake, CONFIGS[5], slices=[(0, 0, 0), (40, 2, 4), (63, 3, 7)], pref_layers=[(63, 1)])
+
+
+def test_config2_full_cascade_equals_one_shot(cake):
+    # Alg. 1 over all 32 layers at full size: the same caches as the one-shot pass (Thm. 2),
+    # budgets never growing from stage to stage (Prop. 1)
+    cfg = CONFIGS[2]
+    say("full size: config 2 cascade vs one-shot")
+    inp = make_config_inputs(cfg, device=DEV)
+    L, S_w = cfg.n_layers, cfg.window
+    args = ([inp["q_win"][l] for l in range(L)], [inp["k"][l] for l in range(L)], [inp["v"][l] for l in range(L)])
+    shot = cake.EvictionPass(*args, cfg.total_budget).run()
+    torch.cuda.synchronize()
+    shot_k = [t.clone() for t in shot.k_out]
+    shot_idx = [t.clone() for t in shot.idx]
+    casc = cake.EvictionPass(*args, cfg.total_budget).run_cascade()
+    np.testing.assert_array_equal(casc.budgets, shot.budgets)
+    assert casc.budgets.sum() == cfg.total_budget
+    for m in range(1, L):
+        assert np.all(casc.stage_budgets[m][:m] <= casc.stage_budgets[m - 1])
+    for l in range(L):
+        n_k = int(shot.keep[l, 0])
+        assert torch.equal(casc.idx[l][0, :, :n_k], shot_idx[l][0, :, :n_k])
+        assert torch.equal(casc.k_out[l][0, :, : n_k + S_w], shot_k[l][0, :, : n_k + S_w])
