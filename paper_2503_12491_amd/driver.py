@@ -189,6 +189,16 @@ class EvictionPass:
         return res
 
 
+class _Held:
+    """Where a layer's current cache lives: raw device addresses into the caller's tensors or into a
+    slab this session allocated, the element strides of K/V, the row capacity, and the owners that
+    keep the memory alive."""
+    __slots__ = ("k", "v", "ind", "strides", "cap", "owners", "views")
+
+    def __init__(self, k, v, ind, strides, cap, owners, views):
+        self.k, self.v, self.ind, self.strides, self.cap, self.owners, self.views = k, v, ind, strides, cap, owners, views
+
+
 class CascadeSession:
     """Alg. 1 as the prefill produces its layers: `admit` takes layer m's window queries, keys and
     values when the forward pass reaches it, scores the layer, recomputes B^(m) over the layers seen
@@ -198,7 +208,13 @@ class CascadeSession:
     the caller's K/V of a layer only until that layer's first eviction, so after every stage it
     holds at most B_total rows per head in all (Sec. 4.2: the prefill's peak stays at the budget
     plus the layer being admitted).  With `track_positions` the retained rows' original prefix
-    positions are carried along (index bookkeeping with torch.gather, not part of the method)."""
+    positions are carried along (index bookkeeping with torch.gather, not part of the method).
+
+    Per stage the host does one pinned read-back of the new layer's preference, the allocation,
+    one upload of all pointer tables and four slab allocations (the outputs of every affected layer
+    are carved from them); nothing else touches the allocator or the copy engine."""
+
+    _ROWS = 10      # pointer tables per stage: q, k, ind (scores); ind_in, idx, k_in, v_in, k_out, v_out, i_out
 
     def __init__(self, n_layers: int, total_budget: int, params=None, track_positions: bool = True):
         self.L = int(n_layers)
@@ -206,9 +222,7 @@ class CascadeSession:
         self.params = params if params is not None else C.make_params()
         self.track_positions = track_positions
         self.m = 0                                     # layers admitted so far
-        self.cur_k: List[torch.Tensor] = []            # current caches [B,H_kv,cap+S_w,d]
-        self.cur_v: List[torch.Tensor] = []
-        self.cur_i: List[torch.Tensor] = []            # current indicators [B,H_kv,cap]
+        self.held: List[_Held] = []
         self.cur_pos: List[Optional[torch.Tensor]] = []
         self.stage_budgets: list = []
         self.budgets = None
@@ -217,18 +231,25 @@ class CascadeSession:
     def _setup(self, q_win, k):
         B, H_q, S_w, d = q_win.shape
         H_kv, N = k.shape[1], k.shape[2]
-        self._geom = (B, H_q, H_kv, S_w, d, N, k.dtype, k.device)
+        dev = k.device
+        self._geom = (B, H_q, H_kv, S_w, d, N, k.dtype, dev)
         self.shape1 = C.make_shape(B, 1, H_q, H_kv, d, N, S_w, k.dtype)
-        self.ws1 = torch.empty(C.cake_workspace_bytes(self.shape1), dtype=torch.uint8, device=k.device)
-        self.pref1 = torch.empty(B, 1, dtype=torch.float64, device=k.device)
-        self.hv1 = torch.empty(B, 1, 2, dtype=torch.float64, device=k.device)
+        self.ws1 = torch.empty(C.cake_workspace_bytes(self.shape1), dtype=torch.uint8, device=dev)
+        self.pref1 = torch.empty(3 * B, dtype=torch.float64, device=dev)       # P [B], then (H, V) [B, 2]
+        self.pref1_host = torch.empty(3 * B, dtype=torch.float64).pin_memory()
         self.pref = np.zeros((B, self.L))
         self.hv = np.zeros((B, self.L, 2))
         self.cur_len = np.zeros((self.L, B), dtype=np.int64)
+        # pointer tables: two pinned staging copies (a stage's upload has certainly run by the time
+        # the stage after next refills the same copy: every stage waits for its read-back) and one
+        # device copy per parity
+        self.tbl_host = [torch.zeros(self._ROWS, self.L, dtype=torch.int64).pin_memory() for _ in range(2)]
+        self.tbl_dev = [torch.zeros(self._ROWS, self.L, dtype=torch.int64, device=dev) for _ in range(2)]
+        self.elem = torch.empty(0, dtype=k.dtype).element_size()
 
     def rows_held(self) -> int:
         """Cache rows per KV head and sequence that the session holds now (window rows included)."""
-        return int(sum(t.shape[2] for t in self.cur_k))
+        return int(sum(h.cap + self._geom[3] for h in self.held))
 
     def admit(self, q_win: torch.Tensor, k: torch.Tensor, v: torch.Tensor, row_lse: Optional[torch.Tensor] = None,
               indicator_out: Optional[torch.Tensor] = None) -> np.ndarray:
@@ -238,20 +259,29 @@ class CascadeSession:
             self._setup(q_win, k)
         B, H_q, H_kv, S_w, d, N, dtype, dev = self._geom
         assert tuple(q_win.shape) == (B, H_q, S_w, d) and tuple(k.shape) == (B, H_kv, N, d) and v.shape == k.shape
+        assert _strides3(v) == _strides3(k)
         N_p, m = N - S_w, self.m
+        host, devt = self.tbl_host[m & 1], self.tbl_dev[m & 1]
+        th = host.numpy()
         # ---- admit layer m: indicator and preference
         ind = indicator_out if indicator_out is not None else torch.empty(B, H_kv, N_p, dtype=torch.float32, device=dev)
-        t_q, t_k, t_i = C.ptr_table([q_win]), C.ptr_table([k]), C.ptr_table([ind])
-        if row_lse is None:
-            C.cake_window_scores(self.shape1, self.params, t_q, t_k, _strides3(q_win), _strides3(k), t_i, self.ws1)
+        lse = None if row_lse is None else row_lse.contiguous()
+        th[0, 0], th[1, 0], th[2, 0] = q_win.data_ptr(), k.data_ptr(), ind.data_ptr()
+        th[3, 0] = 0 if lse is None else lse.data_ptr()
+        devt.copy_(host, non_blocking=True)
+        if lse is None:
+            C.cake_window_scores(self.shape1, self.params, devt[0], devt[1], _strides3(q_win), _strides3(k), devt[2], self.ws1)
         else:
-            lse = row_lse.contiguous()
-            C.cake_window_scores_lse(self.shape1, self.params, t_q, t_k, _strides3(q_win), _strides3(k),
-                                     C.ptr_table([lse]), t_i, self.ws1)
-        C.cake_layer_preference(self.shape1, self.params, self.ws1, self.pref1, self.hv1)
-        self.pref[:, m] = self.pref1.cpu().numpy()[:, 0]
-        self.hv[:, m] = self.hv1.cpu().numpy()[:, 0]
-        self.cur_k.append(k); self.cur_v.append(v); self.cur_i.append(ind)
+            C.cake_window_scores_lse(self.shape1, self.params, devt[0], devt[1], _strides3(q_win), _strides3(k),
+                                     devt[3], devt[2], self.ws1)
+        C.cake_layer_preference(self.shape1, self.params, self.ws1, self.pref1[:B], self.pref1[B:])
+        self.pref1_host.copy_(self.pref1, non_blocking=True)
+        torch.cuda.current_stream().synchronize()
+        got = self.pref1_host.numpy()
+        self.pref[:, m] = got[:B]
+        self.hv[:, m] = got[B:].reshape(B, 2)
+        self.held.append(_Held(k.data_ptr(), v.data_ptr(), ind.data_ptr(), _strides3(k), N_p, (k, v, ind, lse),
+                               (k, v, ind)))
         self.cur_len[m, :] = N_p
         self.cur_pos.append(torch.arange(N_p, device=dev, dtype=torch.int64).expand(B, H_kv, N_p)
                             if self.track_positions else None)
@@ -263,44 +293,72 @@ class CascadeSession:
         self.budgets = budgets
         self.stage_budgets.append(budgets.copy())
         keep = np.minimum(np.maximum(budgets - S_w, 0), self.cur_len[: m + 1])
-        layers = [l for l in range(m + 1) if np.any(keep[l] < self.cur_len[l])]
+        layers = np.nonzero((keep < self.cur_len[: m + 1]).any(axis=1))[0].tolist()
         if not layers:
             return budgets
-        # ---- EVICT the affected layers in one batched call each
+        # ---- EVICT the affected layers in one batched call each; outputs carved from four slabs
         n = len(layers)
         shape_n = C.make_shape(B, n, H_q, H_kv, d, N, S_w, dtype)
-        caps = [int(keep[l].max()) for l in layers]
+        caps = keep[layers].max(axis=1)                                   # row capacity of each output
+        caps1 = np.maximum(caps, 1)
+        bh = B * H_kv
+        off_kv = np.concatenate([[0], np.cumsum((caps + S_w) * (bh * d))])
+        off_i = np.concatenate([[0], np.cumsum(caps1 * bh)])
+        k_slab = torch.empty(int(off_kv[-1]), dtype=dtype, device=dev)
+        v_slab = torch.empty(int(off_kv[-1]), dtype=dtype, device=dev)
+        i_slab = torch.empty(int(off_i[-1]), dtype=torch.float32, device=dev)
         # zero-filled: with a ragged batch the entries past a sequence's own count are never
         # written by the library, and the position bookkeeping below gathers through them
-        idx = [torch.zeros(B, H_kv, max(c, 1), dtype=torch.int32, device=dev) for c in caps]
-        k_out = [torch.empty(B, H_kv, c + S_w, d, dtype=dtype, device=dev) for c in caps]
-        v_out = [torch.empty_like(t) for t in k_out]
-        i_out = [torch.empty(B, H_kv, max(c, 1), dtype=torch.float32, device=dev) for c in caps]
-        cl = [int(x) for l in layers for x in self.cur_len[l]]
-        kk = [int(x) for l in layers for x in keep[l]]
-        t_idx = C.ptr_table(idx)
-        t_ind = C.ptr_table([self.cur_i[l] for l in layers])
-        C.cake_select_topk(shape_n, t_ind, cl, kk, t_idx)
-        C.cake_compact_kv(shape_n, C.ptr_table([self.cur_k[l] for l in layers]),
-                          C.ptr_table([self.cur_v[l] for l in layers]),
-                          [_strides3(self.cur_k[l]) for l in layers], cl, kk, t_idx, t_ind, C.ptr_table(k_out),
-                          C.ptr_table(v_out), C.ptr_table(i_out))
+        idx_slab = (torch.zeros if self.track_positions and B > 1 else torch.empty)(
+            int(off_i[-1]), dtype=torch.int32, device=dev)
+        kb, vb, ib, xb = k_slab.data_ptr(), v_slab.data_ptr(), i_slab.data_ptr(), idx_slab.data_ptr()
+        strides, cl, kk = [], [], []
         for j, l in enumerate(layers):
+            h = self.held[l]
+            th[3, j], th[5, j], th[6, j] = h.ind, h.k, h.v
+            th[4, j] = xb + int(off_i[j]) * 4
+            th[7, j] = kb + int(off_kv[j]) * self.elem
+            th[8, j] = vb + int(off_kv[j]) * self.elem
+            th[9, j] = ib + int(off_i[j]) * 4
+            strides.append(h.strides)
+        cl = self.cur_len[layers].reshape(-1).tolist()
+        kk = keep[layers].reshape(-1).tolist()
+        devt.copy_(host, non_blocking=True)
+        C.cake_select_topk(shape_n, devt[3], cl, kk, devt[4])
+        C.cake_compact_kv(shape_n, devt[5], devt[6], strides, cl, kk, devt[4], devt[3], devt[7], devt[8], devt[9])
+        for j, l in enumerate(layers):
+            c, c1 = int(caps[j]), int(caps1[j])
             if self.track_positions:
-                c = caps[j]
-                self.cur_pos[l] = (torch.gather(self.cur_pos[l], 2, idx[j][:, :, :c].long()) if c
+                idx_j = idx_slab[int(off_i[j]): int(off_i[j + 1])].view(B, H_kv, c1)
+                self.cur_pos[l] = (torch.gather(self.cur_pos[l], 2, idx_j[:, :, :c].long()) if c
                                    else self.cur_pos[l][:, :, :0])
-            self.cur_k[l], self.cur_v[l], self.cur_i[l] = k_out[j], v_out[j], i_out[j]
+            rows = c + S_w
+            self.held[l] = _Held(int(th[7, j]), int(th[8, j]), int(th[9, j]), [H_kv * rows * d, rows * d, d], c,
+                                 (k_slab, v_slab, i_slab), None)
+            self.held[l].views = (k_slab, v_slab, i_slab, int(off_kv[j]), int(off_i[j]), c1)
             self.cur_len[l] = keep[l]
         return budgets
+
+    def _layer_views(self, l: int):
+        B, H_q, H_kv, S_w, d, N, dtype, dev = self._geom
+        h = self.held[l]
+        if len(h.views) == 3:                         # still the caller's tensors and the full indicator
+            return h.views
+        k_slab, v_slab, i_slab, o_kv, o_i, c1 = h.views
+        rows = h.cap + S_w
+        n_kv = B * H_kv * rows * d
+        return (k_slab[o_kv: o_kv + n_kv].view(B, H_kv, rows, d), v_slab[o_kv: o_kv + n_kv].view(B, H_kv, rows, d),
+                i_slab[o_i: o_i + B * H_kv * c1].view(B, H_kv, c1))
 
     def result(self) -> PassResult:
         """The caches, indicators and (if tracked) original positions after the stages so far."""
         torch.cuda.synchronize()
         m = self.m
+        views = [self._layer_views(l) for l in range(m)]
         idx_final = [p.to(torch.int32) if p is not None else None for p in self.cur_pos]
         return PassResult(self.budgets, self.cur_len[:m].copy(), self.pref[:, :m].copy(), self.hv[:, :m].copy(), [],
-                          idx_final, list(self.cur_k), list(self.cur_v), list(self.cur_i), list(self.stage_budgets))
+                          idx_final, [t[0] for t in views], [t[1] for t in views], [t[2] for t in views],
+                          list(self.stage_budgets))
 
 
 class DecodeCache:
