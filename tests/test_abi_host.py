@@ -112,6 +112,26 @@ def test_shape_and_argument_errors_are_reported_on_the_host(cake):
     assert rc == -1
     rc = C.load().cake_layer_preference(ctypes.byref(ok), ctypes.byref(params), None, 0, None, None, None)
     assert rc == -1
+    rc = C.load().cake_window_scores_lse(ctypes.byref(ok), ctypes.byref(params), None, None, None, None, None, None, None, 0, None)
+    assert rc == -1 and b"row_lse" in C.load().cake_last_error()
+    rc = C.load().cake_decode_update(ctypes.byref(ok), ctypes.byref(params), None, None, None, None, None, None, None, 0, None)
+    assert rc == -1 and b"NULL" in C.load().cake_last_error()
+    # parameter checks: indicator mode, pooling width, decode lengths beyond the cache capacity
+    one = (ctypes.c_int64 * 3)(64, 64, 64)
+    tbl = ctypes.c_void_p(256)                      # never dereferenced: the call fails before any launch
+    bad_mode = cake.make_params(indicator_mode=9)
+    rc = C.load().cake_window_scores(ctypes.byref(ok), ctypes.byref(bad_mode), tbl, tbl, one, one, tbl, tbl, 1 << 30, None)
+    assert rc == -1 and b"indicator_mode" in C.load().cake_last_error()
+    bad_pool = cake.make_params(pool_kernel=4)
+    rc = C.load().cake_window_scores(ctypes.byref(ok), ctypes.byref(bad_pool), tbl, tbl, one, one, tbl, tbl, 1 << 30, None)
+    assert rc == -1 and b"pool_kernel" in C.load().cake_last_error()
+    too_long = (ctypes.c_int32 * 2)(1024, 10)        # cur_len > seq_len - window
+    two = (ctypes.c_int64 * 2)(256, 64)
+    six = (ctypes.c_int64 * 6)(64, 64, 64, 64, 64, 64)
+    rc = C.load().cake_decode_update(ctypes.byref(ok), ctypes.byref(params), tbl, two, tbl, six, too_long, tbl, tbl, 1 << 30, None)
+    assert rc == -1 and b"cur_len" in C.load().cake_last_error()
+    rc = C.load().cake_window_scores(ctypes.byref(ok), ctypes.byref(params), tbl, tbl, one, one, tbl, tbl, 16, None)
+    assert rc == -3                                   # workspace too small
 
 
 def test_workspace_grows_with_the_problem(cake):
