@@ -3,13 +3,14 @@
 // window is pooled and folded into the stored eviction indicator; the layer is then evicted
 // back to its fixed budget with cake_select_topk / cake_compact_kv at k = cur_len - 1).
 //
-// One workgroup per (layer, sequence, KV head).  The cache of that head holds cur_len scored
-// rows followed by the S_w window rows, the last of which is the new token's key.  The G query
-// heads of the group attend to all cur_len + S_w rows (one query row each: a matrix-vector
-// product, done on the vector ALU); the weights on the scored rows are averaged over the group,
-// max-pooled along the row axis and added to the stored indicator.  Caches at their budget are a
-// few thousand rows per head, so the kernel is latency-bound by design; the keys are read
-// twice (normaliser, then weights) rather than keeping G logits per row.
+// The cache of a (layer, sequence, KV head) holds cur_len scored rows followed by the S_w window
+// rows, the last of which is the new token's key.  The G query heads of the group attend to all
+// cur_len + S_w rows (one query row each: a matrix-vector product, done on the vector ALU, one
+// row per thread); the weights on the scored rows are averaged over the group, max-pooled along
+// the row axis and added to the stored indicator.  Two launches over chunks of 256 rows, so
+// that a few thousand rows per head still spread over the chip: per-chunk softmax partials, then
+// normaliser + weights (with the pooling halo recomputed) + update.  The keys are read twice
+// rather than keeping G logits per row.
 #include <algorithm>
 #include <cmath>
 
@@ -22,6 +23,7 @@ constexpr int kThreads = 256;
 constexpr int kWaves = kThreads / 64;
 constexpr int kMaxGroup = 8;
 constexpr float kMasked = -1.0e30f;
+constexpr int kMaxHalf = 64;               // widest pooling window: 2*64+1
 
 struct DecodeArgs {
   const void* const* q_new;
@@ -29,10 +31,10 @@ struct DecodeArgs {
   float* const* indicator;
   int64_t qs[2];             // element strides of q_new: batch, head
   int32_t batch, h_kv, group, window, pool;
-  int32_t obs_stride;        // floats per slice in `obs`
+  int32_t n_chunks;          // chunks of kThreads rows per slice in `part`
   float c;                   // scale * log2(e)
   float inv_g;
-  float* obs;                // [slice][obs_stride]: group-mean weights on the scored rows
+  float* part;               // [slice][n_chunks][kMaxGroup][2]: (reference, sum) of each chunk and head
   int32_t cap_cur[kMaxLaunchLayers];
 };
 
@@ -77,38 +79,30 @@ __device__ __forceinline__ void row_logits(const T* k_row, const float* q_lds, i
   for (int h = 0; h < kMaxGroup; ++h) t[h] = acc[h] * c;
 }
 
+// Kernel 1: per chunk of kThreads rows and per head, (reference, sum of 2^(t - reference)).
 template <typename T, int D>
-__global__ __launch_bounds__(kThreads) void decode_update_kernel(DecodeArgs a, RaggedDims dims, LayerStrides ks) {
+__global__ __launch_bounds__(kThreads) void decode_partials_kernel(DecodeArgs a, RaggedDims dims, LayerStrides ks) {
   __shared__ float q_lds[kMaxGroup * D];
   __shared__ float red_m[kWaves][kMaxGroup], red_l[kWaves][kMaxGroup];
-  __shared__ float lse_lds[kMaxGroup];
 
-  const int ll = blockIdx.y;
-  const int b = blockIdx.x / a.h_kv, g = blockIdx.x % a.h_kv;
-  const int cur = dims.cur_len[ll * a.batch + b];
-  const int n = cur + a.window;                                  // rows the new query sees
+  const int chunk = blockIdx.x, ll = blockIdx.z;
+  const int b = blockIdx.y / a.h_kv, g = blockIdx.y % a.h_kv;
+  const int n = dims.cur_len[ll * a.batch + b] + a.window;       // rows the new query sees
+  if (chunk * kThreads >= n) return;
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const T* q = reinterpret_cast<const T*>(a.q_new[ll]) + b * a.qs[0] + (int64_t)(g * a.group) * a.qs[1];
   const T* k = reinterpret_cast<const T*>(a.k_cache[ll]) + b * ks.s[ll][0] + g * ks.s[ll][1];
-  const int64_t tok = ks.s[ll][2];
   for (int i = tid; i < a.group * D; i += kThreads) q_lds[i] = (float)q[(i / D) * a.qs[1] + (i % D)];
   __syncthreads();
 
-  // ---- normaliser of every head: running (reference, sum) per thread, then over the workgroup
+  const int j = chunk * kThreads + tid;
   float m[kMaxGroup], l[kMaxGroup];
 #pragma unroll
   for (int h = 0; h < kMaxGroup; ++h) { m[h] = kMasked; l[h] = 0.f; }
-  for (int j = tid; j < n; j += kThreads) {
-    float t[kMaxGroup];
-    row_logits<T, D>(k + j * tok, q_lds, a.group, a.c, t);
+  if (j < n) {
+    row_logits<T, D>(k + j * ks.s[ll][2], q_lds, a.group, a.c, m);
 #pragma unroll
-    for (int h = 0; h < kMaxGroup; ++h) {
-      if (h < a.group) {
-        const float mn = fmaxf(m[h], t[h]);
-        l[h] = l[h] * exp2f(m[h] - mn) + exp2f(t[h] - mn);
-        m[h] = mn;
-      }
-    }
+    for (int h = 0; h < kMaxGroup; ++h) l[h] = 1.f;
   }
 #pragma unroll
   for (int h = 0; h < kMaxGroup; ++h) {
@@ -122,37 +116,66 @@ __global__ __launch_bounds__(kThreads) void decode_update_kernel(DecodeArgs a, R
     if (lane == 0) { red_m[wave][h] = m[h]; red_l[wave][h] = l[h]; }
   }
   __syncthreads();
-  if (tid < kMaxGroup) {
-    float mm = kMasked, s = 0.f;
+  if (tid < a.group) {
+    float mm = kMasked, sum = 0.f;
     for (int w = 0; w < kWaves; ++w) mm = fmaxf(mm, red_m[w][tid]);
-    for (int w = 0; w < kWaves; ++w) s += red_l[w][tid] * exp2f(red_m[w][tid] - mm);
-    lse_lds[tid] = mm + log2f(s);            // heads >= G: never read
+    for (int w = 0; w < kWaves; ++w) sum += red_l[w][tid] * exp2f(red_m[w][tid] - mm);
+    float* o = a.part + ((((int64_t)(ll * a.batch + b) * a.h_kv + g) * a.n_chunks + chunk) * kMaxGroup + tid) * 2;
+    o[0] = mm;
+    o[1] = sum;
+  }
+}
+
+// Kernel 2: normalisers from the chunks' pairs, then for this chunk's scored rows (and the pooling
+// halo on either side) the group-mean weights, pooled and added to the stored indicator.
+template <typename T, int D>
+__global__ __launch_bounds__(kThreads) void decode_apply_kernel(DecodeArgs a, RaggedDims dims, LayerStrides ks) {
+  __shared__ float q_lds[kMaxGroup * D];
+  __shared__ float lse_lds[kMaxGroup];
+  __shared__ float obs[kThreads + 2 * kMaxHalf];
+
+  const int chunk = blockIdx.x, ll = blockIdx.z;
+  const int b = blockIdx.y / a.h_kv, g = blockIdx.y % a.h_kv;
+  const int cur = dims.cur_len[ll * a.batch + b];
+  const int n = cur + a.window;
+  if (chunk * kThreads >= cur) return;
+  const int tid = threadIdx.x;
+  const T* q = reinterpret_cast<const T*>(a.q_new[ll]) + b * a.qs[0] + (int64_t)(g * a.group) * a.qs[1];
+  const T* k = reinterpret_cast<const T*>(a.k_cache[ll]) + b * ks.s[ll][0] + g * ks.s[ll][1];
+  for (int i = tid; i < a.group * D; i += kThreads) q_lds[i] = (float)q[(i / D) * a.qs[1] + (i % D)];
+  if (tid < a.group) {
+    const int used = (n + kThreads - 1) / kThreads;               // chunks that hold rows
+    const float* p = a.part + (((int64_t)(ll * a.batch + b) * a.h_kv + g) * a.n_chunks * kMaxGroup + tid) * 2;
+    float mm = kMasked;
+    for (int c = 0; c < used; ++c) mm = fmaxf(mm, p[(int64_t)c * kMaxGroup * 2]);
+    float sum = 0.f;
+    for (int c = 0; c < used; ++c) sum += p[(int64_t)c * kMaxGroup * 2 + 1] * exp2f(p[(int64_t)c * kMaxGroup * 2] - mm);
+    lse_lds[tid] = mm + log2f(sum);
   }
   __syncthreads();
 
-  // ---- weights of the scored rows, averaged over the group
-  float* obs = a.obs + (int64_t)((ll * a.batch + b) * a.h_kv + g) * a.obs_stride;
-  for (int j = tid; j < cur; j += kThreads) {
-    float t[kMaxGroup];
-    row_logits<T, D>(k + j * tok, q_lds, a.group, a.c, t);
-    float s = 0.f;
-#pragma unroll
-    for (int h = 0; h < kMaxGroup; ++h)
-      if (h < a.group) s += exp2f(t[h] - lse_lds[h]);
-    obs[j] = s * a.inv_g;
-  }
-  __threadfence_block();
-  __syncthreads();
-
-  // ---- pooled weights are added to the stored indicator
-  float* ind = a.indicator[ll] + ((int64_t)b * a.h_kv + g) * a.cap_cur[ll];
   const int half = a.pool / 2;
-  for (int j = tid; j < cur; j += kThreads) {
-    float mx = obs[j];
-    for (int d = 1; d <= half; ++d) {
-      if (j - d >= 0) mx = fmaxf(mx, obs[j - d]);
-      if (j + d < cur) mx = fmaxf(mx, obs[j + d]);
+  const int j0 = chunk * kThreads - half;                          // first row of the halo
+  for (int i = tid; i < kThreads + 2 * half; i += kThreads) {
+    const int j = j0 + i;
+    float w = -INFINITY;                                           // clipped edges never win the max
+    if (j >= 0 && j < cur) {
+      float t[kMaxGroup];
+      row_logits<T, D>(k + j * ks.s[ll][2], q_lds, a.group, a.c, t);
+      float s = 0.f;
+#pragma unroll
+      for (int h = 0; h < kMaxGroup; ++h)
+        if (h < a.group) s += exp2f(t[h] - lse_lds[h]);
+      w = s * a.inv_g;
     }
+    obs[i] = w;
+  }
+  __syncthreads();
+  const int j = chunk * kThreads + tid;
+  if (j < cur) {
+    float mx = obs[tid + half];
+    for (int d = 1; d <= half; ++d) mx = fmaxf(mx, fmaxf(obs[tid + half - d], obs[tid + half + d]));
+    float* ind = a.indicator[ll] + ((int64_t)b * a.h_kv + g) * a.cap_cur[ll];
     ind[j] += mx;
   }
 }
@@ -188,6 +211,12 @@ extern "C" int cake_decode_update(const cake_shape* shape, const cake_params* pa
     return fail(CAKE_ERR_WORKSPACE, "workspace is NULL or not 256-byte aligned");
   if (workspace_bytes < lay.total)
     return fail(CAKE_ERR_WORKSPACE, "workspace has %zu bytes, %zu needed", workspace_bytes, lay.total);
+  // the chunks' (reference, sum) pairs live where the score pass keeps its own partial pairs
+  const int n_chunks = (shape->seq_len + kThreads - 1) / kThreads;
+  const size_t part_bytes = sizeof(float) * (size_t)lay.n_slices * n_chunks * kMaxGroup * 2;
+  if (lay.off_part + part_bytes > lay.total)
+    return fail(CAKE_ERR_WORKSPACE, "workspace layout leaves %zu bytes for the decode partials, %zu needed",
+                lay.total - lay.off_part, part_bytes);
   hipStream_t st = static_cast<hipStream_t>(stream);
   const double scale = params->scale > 0.f ? (double)params->scale : 1.0 / std::sqrt((double)shape->head_dim);
   for (int l0 = 0; l0 < L;) {
@@ -198,10 +227,12 @@ extern "C" int cake_decode_update(const cake_shape* shape, const cake_params* pa
     a.q_new = q_new + l0; a.k_cache = k_cache + l0; a.indicator = indicator + l0;
     a.qs[0] = q_strides[0]; a.qs[1] = q_strides[1];
     a.batch = B; a.h_kv = shape->n_kv_heads; a.group = G; a.window = shape->window; a.pool = params->pool_kernel;
-    a.obs_stride = n_p;
+    a.n_chunks = n_chunks;
     a.c = (float)(scale * 1.4426950408889634);
     a.inv_g = 1.0f / (float)G;
-    a.obs = reinterpret_cast<float*>(static_cast<char*>(workspace) + lay.off_raw) + (int64_t)l0 * B * shape->n_kv_heads * n_p;
+    a.part = reinterpret_cast<float*>(static_cast<char*>(workspace) + lay.off_part) +
+             (int64_t)l0 * B * shape->n_kv_heads * n_chunks * kMaxGroup * 2;
+    int max_cur = 0;
     for (int ll = 0; ll < nl; ++ll) {
       int cc = 0;
       for (int b = 0; b < B; ++b) {
@@ -209,10 +240,16 @@ extern "C" int cake_decode_update(const cake_shape* shape, const cake_params* pa
         cc = std::max(cc, cur_len[(l0 + ll) * B + b]);
       }
       a.cap_cur[ll] = cc;
+      max_cur = std::max(max_cur, cc);
       for (int i = 0; i < 3; ++i) ks.s[ll][i] = k_strides[(l0 + ll) * 3 + i];
     }
-    dim3 grid(B * shape->n_kv_heads, nl), block(kThreads);
-#define CAKE_DECODE(T, D) hipLaunchKernelGGL((decode_update_kernel<T, D>), grid, block, 0, st, a, dims, ks)
+    const int used = (max_cur + shape->window + kThreads - 1) / kThreads;
+    dim3 grid(used, B * shape->n_kv_heads, nl), block(kThreads);
+#define CAKE_DECODE(T, D)                                                                        \
+  do {                                                                                           \
+    hipLaunchKernelGGL((decode_partials_kernel<T, D>), grid, block, 0, st, a, dims, ks);         \
+    hipLaunchKernelGGL((decode_apply_kernel<T, D>), grid, block, 0, st, a, dims, ks);            \
+  } while (0)
     const bool bf = shape->dtype == CAKE_BF16;
     if (bf && shape->head_dim == 128) CAKE_DECODE(__bf16, 128);
     else if (bf && shape->head_dim == 64) CAKE_DECODE(__bf16, 64);

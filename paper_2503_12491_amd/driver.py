@@ -382,45 +382,65 @@ class DecodeCache:
             self.ind.append(result.ind_out[l][:, :, :cap].contiguous() if cap else
                             result.ind_out[l][:, :, :0].contiguous())
         self._ws = {}
+        self._tbl = None
+        self._step = 0
 
     def step(self, layer: int, q_new: torch.Tensor, k_new: torch.Tensor, v_new: torch.Tensor) -> None:
         """q_new [B, H_q, d]; k_new, v_new [B, H_kv, d]: the generated token's projections at `layer`."""
         l, S_w, B = layer, self.S_w, self.B
         k_old, v_old, i_old = self.k[l], self.v[l], self.ind[l]
         H_kv, d = k_old.shape[1], k_old.shape[3]
+        dev = k_old.device
         cur = self.cur_len[l]
         cap = int(cur.max())
         # ---- append: one more row per sequence; the row that leaves the window starts at 0
-        k_in = torch.empty(B, H_kv, cap + S_w + 1, d, dtype=k_old.dtype, device=k_old.device)
+        k_in = torch.empty(B, H_kv, cap + S_w + 1, d, dtype=k_old.dtype, device=dev)
         v_in = torch.empty_like(k_in)
-        i_in = torch.zeros(B, H_kv, cap + 1, dtype=torch.float32, device=k_old.device)
+        i_in = torch.zeros(B, H_kv, cap + 1, dtype=torch.float32, device=dev)
         k_in[:, :, : cap + S_w] = k_old[:, :, : cap + S_w]
         v_in[:, :, : cap + S_w] = v_old[:, :, : cap + S_w]
         i_in[:, :, :cap] = i_old[:, :, :cap]
-        for b in range(B):
-            n_b = int(cur[b]) + S_w
-            k_in[b, :, n_b] = k_new[b]
-            v_in[b, :, n_b] = v_new[b]
-            i_in[b, :, int(cur[b])] = 0.0
+        if B == 1:
+            k_in[:, :, cap + S_w] = k_new
+            v_in[:, :, cap + S_w] = v_new
+        else:
+            for b in range(B):
+                n_b = int(cur[b]) + S_w
+                k_in[b, :, n_b] = k_new[b]
+                v_in[b, :, n_b] = v_new[b]
+                i_in[b, :, int(cur[b]):] = 0.0
         cur1 = [int(c) + 1 for c in cur]
+        keep = [int(c) for c in cur]
         shape = C.make_shape(B, 1, self.H_q, H_kv, d, cap + S_w + 1, S_w, k_old.dtype)
         key = (B, H_kv, d, cap, str(k_old.dtype))
         if key not in self._ws:
-            self._ws = {key: torch.empty(C.cake_workspace_bytes(shape), dtype=torch.uint8, device=k_old.device)}
+            self._ws = {key: torch.empty(C.cake_workspace_bytes(shape), dtype=torch.uint8, device=dev)}
         ws = self._ws[key]
         q_new = q_new.contiguous()
-        t_i = C.ptr_table([i_in])
-        C.cake_decode_update(shape, self.params, C.ptr_table([q_new]), [q_new.stride(0), q_new.stride(1)],
-                             C.ptr_table([k_in]), [_strides3(k_in)], cur1, t_i, ws)
-        # ---- evict one scored row per head: back to cur rows
-        keep = [int(c) for c in cur]
-        idx = torch.zeros(B, H_kv, max(cap, 1), dtype=torch.int32, device=k_old.device)
-        k_out = torch.empty(B, H_kv, cap + S_w, d, dtype=k_old.dtype, device=k_old.device)
+        idx = torch.zeros(B, H_kv, max(cap, 1), dtype=torch.int32, device=dev)
+        k_out = torch.empty(B, H_kv, cap + S_w, d, dtype=k_old.dtype, device=dev)
         v_out = torch.empty_like(k_out)
-        i_out = torch.empty(B, H_kv, max(cap, 1), dtype=torch.float32, device=k_old.device)
-        t_idx = C.ptr_table([idx])
-        C.cake_select_topk(shape, t_i, cur1, keep, t_idx)
-        C.cake_compact_kv(shape, C.ptr_table([k_in]), C.ptr_table([v_in]), [_strides3(k_in)], cur1, keep, t_idx, t_i,
-                          C.ptr_table([k_out]), C.ptr_table([v_out]), C.ptr_table([i_out]))
+        i_out = torch.empty(B, H_kv, max(cap, 1), dtype=torch.float32, device=dev)
+        # ---- all pointer tables of the step in one upload (two pinned copies used in turn: the
+        # step before last has certainly run, each step's kernels are ordered after its upload)
+        if self._tbl is None:
+            self._tbl = ([torch.zeros(8, dtype=torch.int64).pin_memory() for _ in range(4)],
+                         [torch.zeros(8, dtype=torch.int64, device=dev) for _ in range(4)])
+        slot = self._step & 3
+        if slot == 0 and self._step:
+            torch.cuda.current_stream().synchronize()       # the staging copies are about to be reused
+        self._step += 1
+        host, tbl = self._tbl[0][slot], self._tbl[1][slot]
+        th = host.numpy()
+        th[:] = [q_new.data_ptr(), k_in.data_ptr(), v_in.data_ptr(), i_in.data_ptr(), idx.data_ptr(), k_out.data_ptr(),
+                 v_out.data_ptr(), i_out.data_ptr()]
+        tbl.copy_(host, non_blocking=True)
+        st = [_strides3(k_in)]
+        C.cake_decode_update(shape, self.params, tbl[0:1], [q_new.stride(0), q_new.stride(1)], tbl[1:2], st, cur1,
+                             tbl[3:4], ws)
+        # ---- evict one scored row per head: back to cur rows
+        C.cake_select_topk(shape, tbl[3:4], cur1, keep, tbl[4:5])
+        C.cake_compact_kv(shape, tbl[1:2], tbl[2:3], st, cur1, keep, tbl[4:5], tbl[3:4], tbl[5:6], tbl[6:7], tbl[7:8])
         self.k[l], self.v[l], self.ind[l] = k_out, v_out, i_out[:, :, :cap]
         self.last_idx = idx
+        self._keep_alive = (q_new, k_in, v_in, i_in)       # until the kernels have run
