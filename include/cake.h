@@ -50,8 +50,13 @@ typedef enum {
 
 typedef enum { CAKE_BF16 = 0, CAKE_F32 = 1 } cake_dtype;
 
-/* Problem shape.  Supported: head_dim 64 or 128, window 32 or 64, 1 <= G <= 8,
- * n_layers <= 1024, n_layers * batch unbounded (large passes are split into launches). */
+/* Problem shape.  Supported: head_dim 64 or 128, window 32 or 64, 1 <= G <= 8, n_layers <= 1024,
+ * batch <= 256, batch * n_kv_heads <= 65535, and for the score calls
+ * n_layers * batch * n_kv_heads <= 65535 per call (split larger passes over layers).  The top-k,
+ * compaction and decode calls split their launches over layers themselves.
+ * Every per-layer base pointer in a table and every stride must be a multiple of 16 bytes
+ * (rows are moved as 16-byte pieces); the strides are checked, the base pointers live in device
+ * memory and are the caller's responsibility. */
 typedef struct {
   int32_t batch;       /* B */
   int32_t n_layers;    /* layers handled by this call (1 for strict per-layer cascading) */
@@ -90,9 +95,10 @@ int cake_version(void);
 /* Reason for the calling thread's most recent failure; "" if none. */
 const char* cake_last_error(void);
 
-/* Bytes of device workspace that cake_window_scores(_lse), cake_layer_preference,
- * cake_decode_update and cake_select_topk need for `shape` (the maximum over them).  The workspace must be
- * 256-byte aligned.  cake_layer_preference reads what cake_window_scores left in it, so the
+/* Bytes of device workspace that cake_window_scores(_lse) and cake_layer_preference need for
+ * `shape`.  cake_decode_update places its partial sums inside the same layout and checks at
+ * run time that they fit (they do for every supported shape); cake_select_topk needs none.
+ * The workspace must be 256-byte aligned.  cake_layer_preference reads what cake_window_scores left in it, so the
  * same buffer must be passed to both with nothing else written in between. */
 int cake_workspace_bytes(const cake_shape* shape, size_t* bytes /* host, out */);
 
@@ -212,8 +218,8 @@ int cake_compact_kv(const cake_shape* shape,
 /*
  * Indicator maintenance for one generated token (implementation appendix, decoding branch of
  * the listing: the new query's attention over the cached keys outside the window is pooled and
- * the stored indicator is updated with it; "tokens are evicted during both prefilling and
- * decoding", Sec. 5 implementation details).  The paper does not define the update; this
+ * the stored indicator is updated with it; Sec. 5, implementation details: eviction also runs
+ * during decoding).  The paper does not define the update; this
  * library ADDS the pooled weights to the stored values.
  *
  * Sequence b of layer l holds cur_len scored rows followed by its S_w window rows, the last of

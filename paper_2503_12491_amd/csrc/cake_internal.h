@@ -44,7 +44,7 @@ struct ScoreLayout {
   int64_t n_slices;     // L * B * H_kv
   int32_t rows;         // G * S_w window rows per slice
   size_t off_lse;       // f32 [n_slices][rows]            log2-domain row normaliser
-  size_t off_part;      // f32 [n_slices][n_chunks][rows][2][2]   pass-1 (ref, sum) per lane half
+  size_t off_part;      // f32 [n_slices][n_chunks][rows][2]      pass-1 (reference, sum) per window row
   size_t off_hv;        // f32 [n_slices][n_chunks_p][G][2]       pass-2 (entropy, variance) sums
   size_t off_raw;       // f32 [n_slices][N_p]             un-pooled indicator
   size_t total;

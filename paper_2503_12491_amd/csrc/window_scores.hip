@@ -29,6 +29,7 @@
 // combine give way to a kernel that converts them to the log2 domain.
 // Everything is deterministic: no float atomics, fixed reduction orders.
 #include <cmath>
+#include <type_traits>
 
 #include "cake_internal.h"
 
@@ -44,18 +45,6 @@ constexpr int kTileKeys = 64;        // keys staged per LDS tile (two 32-key MFM
 constexpr float kMasked = -1.0e30f;  // stands for -inf without producing NaN in differences
 
 __device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }  // v_exp_f32
-
-// x*c - ref as one v_fma_f32 with this operand order (the accumulator value first, the constant
-// second, all three in vector registers): measured the fastest-issuing form of the instruction;
-// a scalar-register operand or the constant in the first slot lowers the issue rate.
-// The compiler does not see through the statement: it inserts none of the wait states an
-// MFMA result needs before a vector instruction may read it.  Use it only on accumulators whose
-// MFMAs were issued at least a whole sub-tile of instructions earlier.
-__device__ __forceinline__ float scale_minus(float x, float c, float ref) {
-  float t;
-  asm("v_fma_f32 %0, %1, %2, -%3" : "=v"(t) : "v"(x), "v"(c), "v"(ref));
-  return t;
-}
 
 template <typename T, int D>
 struct Tile {
@@ -181,44 +170,49 @@ __device__ __forceinline__ void load_q(typename Frag<T>::type (&qf)[MB][D / Frag
 // ------------------------------------------------------------------------------------------
 // Pass 1: per window row, (reference, sum of 2^(t - reference)) over one chunk of keys.
 // ------------------------------------------------------------------------------------------
-template <typename T, int D, int MB, bool kTail>
-__device__ __forceinline__ void pass1_subtile(const char* tile, int sub, int kb,
-                                              const typename Frag<T>::type (&qf)[MB][D / Frag<T>::kElems],
-                                              float (&mref)[MB], float (&lsum)[MB], float c, int n, int n_p,
-                                              int c32, int hh) {
+// Logits of sub-tile `sub` of `tile` (32 keys) against the wave's window rows.
+// acc[nb][v]: key = kb + 8*(v/4) + 4*hh + (v%4), window row = nb*32 + c32.
+template <typename T, int D, int MB>
+__device__ __forceinline__ void pass1_logits(const char* tile, int sub,
+                                             const typename Frag<T>::type (&qf)[MB][D / Frag<T>::kElems],
+                                             f32x16 (&acc)[MB], int c32, int hh) {
   using F = Frag<T>;
   using TL = Tile<T, D>;
   constexpr int kSteps = D / F::kElems;
-  f32x16 acc[MB];
-#pragma unroll
-  for (int nb = 0; nb < MB; ++nb)
-#pragma unroll
-    for (int v = 0; v < 16; ++v) acc[nb][v] = 0.f;
 #pragma unroll
   for (int s = 0; s < kSteps; ++s) {
-    typename F::type kf = F::template load_lds<TL>(tile, sub * 32 + c32, s, hh);
+    const typename F::type kf = F::template load_lds<TL>(tile, sub * 32 + c32, s, hh);
 #pragma unroll
-    for (int nb = 0; nb < MB; ++nb) acc[nb] = F::mfma(kf, qf[nb][s], acc[nb]);
+    for (int nb = 0; nb < MB; ++nb) {
+      if (s == 0) {
+        f32x16 zero;
+#pragma unroll
+        for (int v = 0; v < 16; ++v) zero[v] = 0.f;
+        acc[nb] = F::mfma(kf, qf[nb][s], zero);
+      } else {
+        acc[nb] = F::mfma(kf, qf[nb][s], acc[nb]);
+      }
+    }
   }
-  // acc[nb][v]: key = kb + 8*(v/4) + 4*hh + (v%4), window row = nb*32 + c32.
-  // Key j is visible to window row r iff j <= n_p + r (and j < n).
+}
+
+// The finished logits of a sub-tile (first key kb) folded into the rows' running
+// (reference, sum) pairs.  Key j is visible to window row r iff j <= n_p + r (and j < n);
+// kTail: some key of the sub-tile may be hidden or lie past the end.
+template <int MB, bool kTail>
+__device__ __forceinline__ void pass1_sums(const f32x16 (&acc)[MB], int kb, float (&mref)[MB], float (&lsum)[MB],
+                                           float cv, int n, int n_p, int c32, int hh) {
 #pragma unroll
   for (int nb = 0; nb < MB; ++nb) {
     const int last_visible = min(n_p + nb * 32 + c32, n - 1);
-    float part[4] = {0.f, 0.f, 0.f, 0.f};     // independent partial sums of the block's 16 terms
+    auto hidden = [&](int v) { return kTail && kb + 8 * (v / 4) + 4 * hh + (v % 4) > last_visible; };
+    float bsum[2] = {0.f, 0.f};           // two chains: consecutive additions do not wait on each other
 #pragma unroll
-    for (int v4 = 0; v4 < 16; v4 += 4) {
-      float e[4];
-#pragma unroll
-      for (int i = 0; i < 4; ++i) e[i] = fast_exp2(acc[nb][v4 + i] * c - mref[nb]);
-#pragma unroll
-      for (int i = 0; i < 4; ++i) {
-        const int v = v4 + i;
-        if (kTail && kb + 8 * (v / 4) + 4 * hh + (v % 4) > last_visible) e[i] = 0.f;
-        part[i] += e[i];
-      }
+    for (int v = 0; v < 16; ++v) {
+      const float e = fast_exp2(fmaf(acc[nb][v], cv, -mref[nb]));
+      bsum[v & 1] += hidden(v) ? 0.f : e;
     }
-    float block = (part[0] + part[1]) + (part[2] + part[3]);
+    float block = bsum[0] + bsum[1];
     // Sixteen terms of at most 2^40 each add at most 2^44.  Anything above that (or inf/NaN)
     // means a logit outran the row's reference: redo the block with a reference of its own.
     const bool lift = !(block <= 16.f * 1.0995116e12f);
@@ -226,18 +220,12 @@ __device__ __forceinline__ void pass1_subtile(const char* tile, int sub, int kb,
       if (lift) {
         float rmax = kMasked;
 #pragma unroll
-        for (int v = 0; v < 16; ++v) {
-          const bool hidden = kTail && kb + 8 * (v / 4) + 4 * hh + (v % 4) > last_visible;
-          rmax = fmaxf(rmax, hidden ? kMasked : acc[nb][v] * c);
-        }
+        for (int v = 0; v < 16; ++v) rmax = fmaxf(rmax, hidden(v) ? kMasked : acc[nb][v] * cv);
         lsum[nb] *= fast_exp2(mref[nb] - rmax);
         mref[nb] = rmax;
         block = 0.f;
 #pragma unroll
-        for (int v = 0; v < 16; ++v) {
-          const bool hidden = kTail && kb + 8 * (v / 4) + 4 * hh + (v % 4) > last_visible;
-          block += hidden ? 0.f : fast_exp2(acc[nb][v] * c - rmax);
-        }
+        for (int v = 0; v < 16; ++v) block += hidden(v) ? 0.f : fast_exp2(acc[nb][v] * cv - rmax);
       }
     }
     lsum[nb] += block;
@@ -249,8 +237,8 @@ __global__ __launch_bounds__(512) void scores_pass1(ScoreArgs a) {
   using F = Frag<T>;
   using TL = Tile<T, D>;
   constexpr int kSteps = D / F::kElems;
-  __shared__ __attribute__((aligned(1024))) char buf0[TL::kBytes];
-  __shared__ __attribute__((aligned(1024))) char buf1[TL::kBytes];
+  // double buffer: tile t+1 is in flight while tile t is consumed (deeper rings measured no faster)
+  __shared__ __attribute__((aligned(1024))) char tiles[2 * TL::kBytes];
 
   const int chunk_id = blockIdx.x, slice = blockIdx.y;
   int l, b, g;
@@ -268,15 +256,28 @@ __global__ __launch_bounds__(512) void scores_pass1(ScoreArgs a) {
   const int n_tiles = (key_end - key0 + kTileKeys - 1) / kTileKeys;
   TileMover<T, D> mover;
   mover.init(kbase, tok_bytes, a.n - 1, w, n_waves, lane);
-  mover.issue(buf0, key0);
+  mover.issue(tiles, key0);
 
   typename F::type qf[MB][kSteps];
   load_q<T, D, MB>(qf, q, a.qs[2], c32, hh);
   float mref[MB], lsum[MB];
 #pragma unroll
   for (int nb = 0; nb < MB; ++nb) { mref[nb] = kMasked; lsum[nb] = 0.f; }
+  float cv = a.c;
+  asm volatile("" : "+v"(cv));     // a vector register: a scalar operand halves the issue rate of the multiply
 
-  auto stage = [&](const char* cur, char* nxt, int t) {
+  // The MFMAs of a 32-key sub-tile, then the exponentials and sums of its logits; with three
+  // waves per SIMD the phases of different waves overlap (an explicit software pipeline over two
+  // accumulator sets measured slower here).
+  f32x16 acc[MB];
+  auto tail_of = [&](int kb) { return kb + 31 > a.n_p; };      // some key of the sub-tile may be hidden or past the end
+
+  // Stage t consumes buffer t mod 2 (known at compile time: the operand reads then address LDS
+  // with immediate offsets) and refills the other one, which stage t-1 consumed.
+  auto stage = [&](auto slot_c, int t) {
+    constexpr int kSlot = decltype(slot_c)::value;
+    const char* cur = tiles + kSlot * TL::kBytes;
+    char* nxt = tiles + (kSlot ^ 1) * TL::kBytes;
     wait_vmem();
     __syncthreads();                 // tile t complete in `cur`; everyone is done reading `nxt`
     const int t0 = key0 + t * kTileKeys;
@@ -285,15 +286,16 @@ __global__ __launch_bounds__(512) void scores_pass1(ScoreArgs a) {
     for (int sub = 0; sub < kTileKeys / 32; ++sub) {
       const int kb = t0 + sub * 32;
       if (kb >= key_end) break;
-      if (kb + 31 > a.n_p)           // some key of this sub-tile may be hidden or past the end
-        pass1_subtile<T, D, MB, true>(cur, sub, kb, qf, mref, lsum, a.c, a.n, a.n_p, c32, hh);
+      pass1_logits<T, D, MB>(cur, sub, qf, acc, c32, hh);
+      if (tail_of(kb))
+        pass1_sums<MB, true>(acc, kb, mref, lsum, cv, a.n, a.n_p, c32, hh);
       else
-        pass1_subtile<T, D, MB, false>(cur, sub, kb, qf, mref, lsum, a.c, a.n, a.n_p, c32, hh);
+        pass1_sums<MB, false>(acc, kb, mref, lsum, cv, a.n, a.n_p, c32, hh);
     }
   };
   for (int t = 0; t < n_tiles; t += 2) {
-    stage(buf0, buf1, t);
-    if (t + 1 < n_tiles) stage(buf1, buf0, t + 1);
+    stage(std::integral_constant<int, 0>{}, t);
+    if (t + 1 < n_tiles) stage(std::integral_constant<int, 1>{}, t + 1);
   }
 
   // Merge the two lane halves of each window row and store the chunk's pair.
@@ -338,39 +340,43 @@ __global__ void scores_import_lse(ScoreArgs a, const float* const* row_lse, int6
 // ------------------------------------------------------------------------------------------
 // Pass 2: normalised weights on the prefix columns; column Mean/Var, entropy, group mean.
 // ------------------------------------------------------------------------------------------
-// Sum of x over the two lane halves, delivered to both.
-__device__ __forceinline__ float add_halves(float x) {
-  auto r = __builtin_amdgcn_permlane32_swap(__float_as_uint(x), __float_as_uint(x), false, false);
-  return __uint_as_float(r[0]) + __uint_as_float(r[1]);
-}
+// Column sums of one finished sub-tile, still split over the two lane halves.
+struct ColSums {
+  float sp, sp2;     // sum of (p - pivot), sum of (p - pivot)^2 over this half's window rows
+  float pivot;       // 0 unless the pivoted form is used
+};
 
-// One period of pass 2's software pipeline.  The MFMAs of sub-tile `sub` of `tile` accumulate
-// into `dst` while the vector ALU turns the finished logits of the previous sub-tile (`src`,
-// first key kb_prev) into weights and column statistics: after every MFMA step comes the share
-// of that work that keeps both pipes busy, and a scheduling barrier pins the interleaving.
-// src[mb][v]: window row mb*32 + 8*(v/4) + 4*hh + (v%4) of key column kb_prev + c32.
-// kSettled: `src` was written by MFMAs of an earlier period (software pipeline), not by the
-// call just before this one.
-template <typename T, int D, int MB, bool kMfma, bool kValu, bool kSettled>
+// One period of pass 2.  kMfma: the MFMAs of sub-tile `sub` of `tile` accumulate into `dst`,
+// starting from `init`, which holds -lse2/c of the lane's window rows, so that the accumulator
+// times c is already the log2 of the weight.  kValu: the finished accumulators in `src` are
+// turned into weights and column sums; with both, the vector work is dealt out over the MFMA
+// steps and a scheduling barrier per step pins the interleaving.
+// src[mb][v]: window row mb*32 + 8*(v/4) + 4*hh + (v%4) of the key column this lane owns.
+// kTail: the column may lie at or beyond the end of the chunk (col_valid false): its weights are
+// forced to zero.  kPivot: the sums are taken about the weight of window row 0 (Var and Mean*Var
+// indicators: sum p^2 - (sum p)^2/S_w would cancel in fp32 where the weights barely move).
+template <typename T, int D, int MB, bool kMfma, bool kValu, bool kTail, bool kPivot>
 __device__ __forceinline__ void pass2_period(const char* tile, int sub,
                                              const typename Frag<T>::type (&qf)[MB][D / Frag<T>::kElems],
-                                             f32x16 (&dst)[MB], const f32x16 (&src)[MB],
-                                             const float (&lse_r)[MB][16], float cv, int kb_prev, int key_end,
-                                             const ScoreArgs& a, float& ent_acc, float& var_acc, float* iq_row,
+                                             const f32x16 (&init)[MB], f32x16 (&dst)[MB], const f32x16 (&src)[MB],
+                                             float cv, bool col_valid, float (&entv)[2], ColSums& out,
                                              int c32, int hh) {
   using F = Frag<T>;
   using TL = Tile<T, D>;
   constexpr int kSteps = D / F::kElems;
   constexpr int kGroups = 4 * MB;      // groups of four logits per lane in a sub-tile
   constexpr int kAhead = 2;            // operand reads in flight ahead of their MFMA step
-  // Four independent accumulator sets: consecutive logits do not wait on each other's adds.
-  float spv[4] = {0.f, 0.f, 0.f, 0.f}, sp2v[4] = {0.f, 0.f, 0.f, 0.f}, entv[4] = {0.f, 0.f, 0.f, 0.f};
+  float spv[2] = {0.f, 0.f}, sp2v[2] = {0.f, 0.f};
+  float pivot = 0.f;
+  auto logit = [&](int mb, int v) { return (kTail && !col_valid) ? -1.0e30f : src[mb][v]; };
+  if (kValu && kPivot) {
+    // the weight of window row 0 lives in the lower lane half (mb 0, v 0); both halves take it
+    const float p0 = fast_exp2(logit(0, 0) * cv);
+    auto r = __builtin_amdgcn_permlane32_swap(__float_as_uint(p0), __float_as_uint(p0), false, false);
+    pivot = __uint_as_float(r[0]);
+  }
   typename F::type kf[kSteps];
   if (kMfma) {
-#pragma unroll
-    for (int mb = 0; mb < MB; ++mb)
-#pragma unroll
-      for (int v = 0; v < 16; ++v) dst[mb][v] = 0.f;
 #pragma unroll
     for (int s = 0; s < kAhead && s < kSteps; ++s) kf[s] = F::template load_lds<TL>(tile, sub * 32 + c32, s, hh);
   }
@@ -379,54 +385,65 @@ __device__ __forceinline__ void pass2_period(const char* tile, int sub,
     if (kMfma) {
       if (s + kAhead < kSteps) kf[s + kAhead] = F::template load_lds<TL>(tile, sub * 32 + c32, s + kAhead, hh);
 #pragma unroll
-      for (int mb = 0; mb < MB; ++mb) dst[mb] = F::mfma(qf[mb][s], kf[s], dst[mb]);
+      for (int mb = 0; mb < MB; ++mb) dst[mb] = F::mfma(qf[mb][s], kf[s], s == 0 ? init[mb] : dst[mb]);
     }
     if (kValu) {
 #pragma unroll
       for (int gi = 0; gi < kGroups; ++gi) {
         if (gi * kSteps / kGroups != s) continue;
         const int mb = gi / 4, v4 = (gi % 4) * 4;
-        float t[4], p[4];
+        float x[4], p[4];
 #pragma unroll
-        for (int i = 0; i < 4; ++i)                                             // log2 of the weight
-          t[i] = kSettled ? scale_minus(src[mb][v4 + i], cv, lse_r[mb][v4 + i]) : src[mb][v4 + i] * cv - lse_r[mb][v4 + i];
+        for (int i = 0; i < 4; ++i) x[i] = logit(mb, v4 + i);
 #pragma unroll
-        for (int i = 0; i < 4; ++i) p[i] = fast_exp2(t[i]);
+        for (int i = 0; i < 4; ++i) p[i] = fast_exp2(x[i] * cv);
 #pragma unroll
         for (int i = 0; i < 4; ++i) {
-          spv[i] += p[i];
-          sp2v[i] = fmaf(p[i], p[i], sp2v[i]);
-          entv[i] = fmaf(p[i], t[i], entv[i]);
+          const float pd = kPivot ? p[i] - pivot : p[i];
+          spv[i & 1] += pd;
+          sp2v[i & 1] = fmaf(pd, pd, sp2v[i & 1]);
+          entv[i & 1] = fmaf(p[i], x[i], entv[i & 1]);      // sum p * log2(p) / c
         }
+        // keep the accumulation in this step (it would otherwise be sunk to the end of the period)
+        asm volatile("" : "+v"(spv[0]), "+v"(spv[1]), "+v"(sp2v[0]), "+v"(sp2v[1]), "+v"(entv[0]), "+v"(entv[1]));
       }
     }
-    __builtin_amdgcn_sched_barrier(0);
+    if (kMfma && kValu) __builtin_amdgcn_sched_barrier(0);
   }
   if (kValu) {
-    const float ent = (entv[0] + entv[1]) + (entv[2] + entv[3]);
-    const float sp = add_halves((spv[0] + spv[1]) + (spv[2] + spv[3]));
-    const float sp2 = add_halves((sp2v[0] + sp2v[1]) + (sp2v[2] + sp2v[3]));
-    const bool valid = kb_prev + c32 < key_end;
-    const float mean = sp * a.inv_sw;
-    const float var = fmaxf((sp2 - sp * mean) * a.inv_swc, 0.f);
-    if (valid) {
-      ent_acc += ent;
-      if (hh == 0) var_acc += var;
-    }
-    const float iq = fmaf(a.w_prod * mean, var, fmaf(a.w_var, var, a.w_mean * mean));
-    if (hh == 0) iq_row[c32] = valid ? iq : 0.f;
+    out.sp = spv[0] + spv[1];
+    out.sp2 = sp2v[0] + sp2v[1];
+    out.pivot = pivot;
   }
 }
 
-template <typename T, int D, int MB>
+// Statistics of the 64 key columns of one tile from the half sums of its two sub-tiles.  One
+// swap of lane halves per quantity leaves lanes 0-31 with the complete sums of sub-tile 0's
+// columns and lanes 32-63 with those of sub-tile 1's: lane L ends up owning key L of the tile.
+template <bool kPivot>
+__device__ __forceinline__ void pass2_tile_stats(const ColSums& s0, const ColSums& s1, const ScoreArgs& a, int hh,
+                                                 float& var_acc, float* iq_row /* [64], this wave's */, int lane) {
+  auto r1 = __builtin_amdgcn_permlane32_swap(__float_as_uint(s0.sp), __float_as_uint(s1.sp), false, false);
+  auto r2 = __builtin_amdgcn_permlane32_swap(__float_as_uint(s0.sp2), __float_as_uint(s1.sp2), false, false);
+  const float sp = __uint_as_float(r1[0]) + __uint_as_float(r1[1]);
+  const float sp2 = __uint_as_float(r2[0]) + __uint_as_float(r2[1]);
+  const float dmean = sp * a.inv_sw;                               // mean of (p - pivot)
+  const float var = fmaxf((sp2 - sp * dmean) * a.inv_swc, 0.f);    // the variance does not see the pivot
+  const float mean = kPivot ? dmean + (hh ? s1.pivot : s0.pivot) : dmean;
+  var_acc += var;
+  iq_row[lane] = fmaf(a.w_prod * mean, var, fmaf(a.w_var, var, a.w_mean * mean));
+}
+
+template <typename T, int D, int MB, bool kPivot>
 __global__ __launch_bounds__(512) void scores_pass2(ScoreArgs a) {
   using F = Frag<T>;
   using TL = Tile<T, D>;
   constexpr int kSteps = D / F::kElems;
-  __shared__ __attribute__((aligned(1024))) char buf0[TL::kBytes];
-  __shared__ __attribute__((aligned(1024))) char buf1[TL::kBytes];
-  // I_q of the G heads for three tiles in rotation: one being read by the flush, two being written
-  __shared__ float iq_lds[3][8][kTileKeys];
+  // double buffer: tile t+1 is in flight while tile t is consumed (deeper rings measured no faster)
+  __shared__ __attribute__((aligned(1024))) char tiles[2 * TL::kBytes];
+  // I_q of the G heads for two tiles in turn: the flush of one tile reads one buffer in the
+  // stage in which the other is written, and a barrier separates the stages
+  __shared__ float iq_lds[2][8][kTileKeys];
 
   const int chunk_id = blockIdx.x, slice = blockIdx.y;
   int l, b, g;
@@ -444,20 +461,24 @@ __global__ __launch_bounds__(512) void scores_pass2(ScoreArgs a) {
   const int n_tiles = (key_end - key0 + kTileKeys - 1) / kTileKeys;
   TileMover<T, D> mover;
   mover.init(kbase, tok_bytes, a.n - 1, w, n_waves, lane);
-  mover.issue(buf0, key0);
+  mover.issue(tiles, key0);
 
   typename F::type qf[MB][kSteps];
   load_q<T, D, MB>(qf, q, a.qs[2], c32, hh);
-  float lse_r[MB][16];
+  // -lse2/c of the lane's window rows, in the accumulator layout: the MFMA chain of a sub-tile
+  // starts from it, so its result times c is the log2 of the normalised weight.
+  f32x16 init[MB];
   const float* lse = a.lse + (int64_t)slice * (a.group * s_w) + w * s_w;
+  const float neg_inv_c = -1.0f / a.c;
 #pragma unroll
   for (int mb = 0; mb < MB; ++mb)
 #pragma unroll
-    for (int v = 0; v < 16; ++v) lse_r[mb][v] = lse[mb * 32 + 8 * (v / 4) + 4 * hh + (v % 4)];
+    for (int v = 0; v < 16; ++v) init[mb][v] = lse[mb * 32 + 8 * (v / 4) + 4 * hh + (v % 4)] * neg_inv_c;
   float cv = a.c;
   asm volatile("" : "+v"(cv));     // a vector register: a scalar operand halves the issue rate of the multiply
 
-  float ent_acc = 0.f, var_acc = 0.f;
+  float entv[2] = {0.f, 0.f};      // sum p * log2(p) / c over this lane's logits, two chains
+  float var_acc = 0.f;
   float* raw = a.raw + (int64_t)slice * a.n_p;
   // Two accumulator sets (logits of even / odd sub-tiles) let one sub-tile's MFMAs overlap the
   // previous one's statistics.  Measured, this pays for bf16 with two row blocks per wave
@@ -466,66 +487,74 @@ __global__ __launch_bounds__(512) void scores_pass2(ScoreArgs a) {
   // phases of a sub-tile one after the other on a single set.
   constexpr bool kPipelined = sizeof(T) == 2 && MB == 2;
   f32x16 acc_a[MB], acc_b[MB];
+  ColSums cs0{}, cs1{};
 
-  // Group mean of the G heads' I_q for the 64 keys of tile t; every wave writes its share of the keys.
-  const int flush_per = (kTileKeys + n_waves - 1) / n_waves;
+  // Group mean of the G heads' I_q for the 64 keys of tile t, one key per lane; the waves take
+  // the tiles in turn.
   auto flush = [&](int t) {
-    const int kl = w * flush_per + lane;                 // key within the tile
-    const int key = key0 + t * kTileKeys + kl;
-    if (lane < flush_per && kl < kTileKeys && key < key_end) {
-      float s = 0.f;
-#pragma unroll
-      for (int ww = 0; ww < 8; ++ww) {
-        const float x = iq_lds[t % 3][ww][kl];           // rows >= G are never written and never used
-        s += ww < a.group ? x : 0.f;
-      }
-      raw[key] = s * a.inv_g;
-    }
+    if (t % n_waves != w) return;
+    const int key = key0 + t * kTileKeys + lane;
+    float s = 0.f;
+    for (int ww = 0; ww < a.group; ++ww) s += iq_lds[t & 1][ww][lane];
+    if (key < key_end) raw[key] = s * a.inv_g;
   };
   // Tile t: its first sub-tile's MFMAs run beside the statistics of tile t-1's second sub-tile,
-  // its second sub-tile's MFMAs beside the statistics of its first.
-  auto stage = [&](const char* cur, char* nxt, int t) {
+  // its second sub-tile's MFMAs beside the statistics of its first.  Only the last tile of a
+  // chunk can hold columns at or beyond key_end.
+  // Stage t consumes buffer t mod 2 (known at compile time: the operand reads then address LDS
+  // with immediate offsets) and refills the other one, which stage t-1 consumed.
+  constexpr int kFlushLag = kPipelined ? 2 : 1;     // stages between a tile's MFMAs and the flush of its I_q
+  auto stage = [&](auto slot_c, int t, auto tail_c) {
+    constexpr int kSlot = decltype(slot_c)::value;
+    constexpr bool kTail = decltype(tail_c)::value;
+    const char* cur = tiles + kSlot * TL::kBytes;
+    char* nxt = tiles + (kSlot ^ 1) * TL::kBytes;
     wait_vmem();
-    __syncthreads();       // tile t complete in `cur`; every wave is done with `nxt` and with tile t-2's I_q
+    __syncthreads();       // tile t complete in `cur`; every wave is done with `nxt` and with the I_q buffer written next
     const int t0 = key0 + t * kTileKeys;
     if (t + 1 < n_tiles) mover.issue(nxt, t0 + kTileKeys);
-    if (t >= 2) flush(t - 2);
+    if (t >= kFlushLag) flush(t - kFlushLag);
+    const bool v0 = t0 + c32 < key_end, v1 = t0 + 32 + c32 < key_end;
     if (kPipelined) {
       if (t == 0) {
-        // the first sub-tile has nothing to run beside; the second one reads its logits straight
-        // after its MFMAs (not settled: the compiler places the wait)
-        pass2_period<T, D, MB, true, false, false>(cur, 0, qf, acc_a, acc_b, lse_r, cv, 0, key_end, a, ent_acc, var_acc, nullptr,
-                                                   c32, hh);
-        pass2_period<T, D, MB, true, true, false>(cur, 1, qf, acc_b, acc_a, lse_r, cv, t0, key_end, a, ent_acc, var_acc,
-                                                  &iq_lds[t % 3][w][0], c32, hh);
+        pass2_period<T, D, MB, true, false, false, kPivot>(cur, 0, qf, init, acc_a, acc_b, cv, true, entv, cs1, c32, hh);
       } else {
-        pass2_period<T, D, MB, true, true, true>(cur, 0, qf, acc_a, acc_b, lse_r, cv, t0 - 32, key_end, a, ent_acc, var_acc,
-                                                 &iq_lds[(t - 1) % 3][w][32], c32, hh);
-        pass2_period<T, D, MB, true, true, true>(cur, 1, qf, acc_b, acc_a, lse_r, cv, t0, key_end, a, ent_acc, var_acc,
-                                                 &iq_lds[t % 3][w][0], c32, hh);
+        // statistics of tile t-1's second sub-tile: never a tail, tile t-1 is not the last
+        pass2_period<T, D, MB, true, true, false, kPivot>(cur, 0, qf, init, acc_a, acc_b, cv, true, entv, cs1, c32, hh);
+        pass2_tile_stats<kPivot>(cs0, cs1, a, hh, var_acc, &iq_lds[(t - 1) & 1][w][0], lane);
       }
+      pass2_period<T, D, MB, true, true, kTail, kPivot>(cur, 1, qf, init, acc_b, acc_a, cv, v0, entv, cs0, c32, hh);
     } else {
-#pragma unroll
-      for (int sub = 0; sub < 2; ++sub) {
-        pass2_period<T, D, MB, true, false, false>(cur, sub, qf, acc_a, acc_a, lse_r, cv, 0, key_end, a, ent_acc, var_acc, nullptr, c32, hh);
-        pass2_period<T, D, MB, false, true, false>(cur, sub, qf, acc_a, acc_a, lse_r, cv, t0 + sub * 32, key_end, a, ent_acc, var_acc,
-                                            &iq_lds[t % 3][w][sub * 32], c32, hh);
-      }
+      pass2_period<T, D, MB, true, false, false, kPivot>(cur, 0, qf, init, acc_a, acc_a, cv, true, entv, cs0, c32, hh);
+      pass2_period<T, D, MB, false, true, kTail, kPivot>(cur, 0, qf, init, acc_a, acc_a, cv, v0, entv, cs0, c32, hh);
+      pass2_period<T, D, MB, true, false, false, kPivot>(cur, 1, qf, init, acc_a, acc_a, cv, true, entv, cs1, c32, hh);
+      pass2_period<T, D, MB, false, true, kTail, kPivot>(cur, 1, qf, init, acc_a, acc_a, cv, v1, entv, cs1, c32, hh);
+      pass2_tile_stats<kPivot>(cs0, cs1, a, hh, var_acc, &iq_lds[t & 1][w][0], lane);
     }
   };
+  const bool last_partial = (key_end - key0) % kTileKeys != 0;
+  auto stage_at = [&](auto slot_c, int t) {
+    if (t + 1 == n_tiles && last_partial) stage(slot_c, t, std::true_type{});
+    else stage(slot_c, t, std::false_type{});
+  };
   for (int t = 0; t < n_tiles; t += 2) {
-    stage(buf0, buf1, t);
-    if (t + 1 < n_tiles) stage(buf1, buf0, t + 1);
+    stage_at(std::integral_constant<int, 0>{}, t);
+    if (t + 1 < n_tiles) stage_at(std::integral_constant<int, 1>{}, t + 1);
   }
-  // drain: statistics of the last sub-tile
-  if (kPipelined)
-    pass2_period<T, D, MB, false, true, true>(buf0, 0, qf, acc_a, acc_b, lse_r, cv, key0 + (n_tiles - 1) * kTileKeys + 32, key_end, a,
-                                      ent_acc, var_acc, &iq_lds[(n_tiles - 1) % 3][w][32], c32, hh);
+  if (kPipelined) {    // drain: statistics of the last sub-tile, then of the last tile
+    const bool v1 = key0 + (n_tiles - 1) * kTileKeys + 32 + c32 < key_end;
+    if (last_partial)
+      pass2_period<T, D, MB, false, true, true, kPivot>(tiles, 0, qf, init, acc_a, acc_b, cv, v1, entv, cs1, c32, hh);
+    else
+      pass2_period<T, D, MB, false, true, false, kPivot>(tiles, 0, qf, init, acc_a, acc_b, cv, true, entv, cs1, c32, hh);
+    pass2_tile_stats<kPivot>(cs0, cs1, a, hh, var_acc, &iq_lds[(n_tiles - 1) & 1][w][0], lane);
+  }
   __syncthreads();
-  if (n_tiles >= 2) flush(n_tiles - 2);
+  if (kFlushLag == 2 && n_tiles >= 2) flush(n_tiles - 2);
   flush(n_tiles - 1);
 
   // Per-wave sums in a fixed order.
+  float ent_acc = (entv[0] + entv[1]) * cv;
 #pragma unroll
   for (int off = 32; off >= 1; off >>= 1) {
     ent_acc += __shfl_xor(ent_acc, off);
@@ -586,8 +615,10 @@ __global__ void layer_preference_kernel(const float* hv, int n_layers, int batch
   }
   if (lane == 0) {
     const double heads = (double)(h_kv * group);
-    const double h_l = -0.6931471805599453 * e / heads;   // sum p*log2 p -> -sum p ln p
-    const double v_l = v / heads;
+    // Both are non-negative by definition; with nearly one-hot attention the fp32 sums can come
+    // out a rounding error below zero, which the fractional powers below would turn into NaN.
+    const double h_l = fmax(-0.6931471805599453 * e / heads, 0.0);   // sum p*log2 p -> -sum p ln p
+    const double v_l = fmax(v / heads, 0.0);
     pref[(int64_t)b * n_layers + l] = pow(h_l, inv_tau1) * pow(v_l, inv_tau2);
     if (hv_out) {
       hv_out[((int64_t)b * n_layers + l) * 2 + 0] = h_l;
@@ -607,7 +638,7 @@ inline void mark(int i, hipStream_t stream) {
   if (g_profile.enabled && g_profile.created) (void)hipEventRecord(g_profile.ev[i], stream);
 }
 
-template <typename T, int D, int MB>
+template <typename T, int D, int MB, bool kPivot>
 int launch_scores(const ScoreArgs& a, int64_t n_slices, const float* const* row_lse, hipStream_t stream) {
   dim3 block(64 * a.group);
   const int rows = a.group * MB * 32;
@@ -624,7 +655,7 @@ int launch_scores(const ScoreArgs& a, int64_t n_slices, const float* const* row_
     mark(1, stream);
   }
   mark(2, stream);
-  hipLaunchKernelGGL((scores_pass2<T, D, MB>), dim3(a.n_chunks_p, (unsigned)n_slices), block, 0, stream, a);
+  hipLaunchKernelGGL((scores_pass2<T, D, MB, kPivot>), dim3(a.n_chunks_p, (unsigned)n_slices), block, 0, stream, a);
   mark(3, stream);
   hipLaunchKernelGGL(pool_indicator, dim3((a.n_p + kPoolSpan - 1) / kPoolSpan, (unsigned)n_slices), dim3(256), 0, stream, a);
   mark(4, stream);
@@ -712,7 +743,12 @@ int window_scores_impl(const cake_shape* shape, const cake_params* params,
   a.raw = reinterpret_cast<float*>(ws + lay.off_raw);
   hipStream_t st = static_cast<hipStream_t>(stream);
 
-#define CAKE_DISPATCH(T, D, MB) return launch_scores<T, D, MB>(a, lay.n_slices, row_lse, st)
+  // Var and Mean*Var score a token by the variance alone or by a product with it: those take the
+  // pivoted column sums.  Eq. 11's sum and the plain mean do not need them.
+  const bool pivot = mode == CAKE_IND_VAR || mode == CAKE_IND_MEAN_TIMES_VAR;
+#define CAKE_DISPATCH(T, D, MB)                                                         \
+  return pivot ? launch_scores<T, D, MB, true>(a, lay.n_slices, row_lse, st)            \
+               : launch_scores<T, D, MB, false>(a, lay.n_slices, row_lse, st)
   const bool bf = shape->dtype == CAKE_BF16;
   const int d = shape->head_dim, mb = shape->window / 32;
   if (bf && d == 128 && mb == 1) CAKE_DISPATCH(__bf16, 128, 1);

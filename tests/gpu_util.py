@@ -76,7 +76,9 @@ def assert_topk_within_ties(got_idx, oracle_ind_row, k, rtol=RTOL):
     diff = np.setxor1d(got, want)
     if diff.size:
         vals = oracle_ind_row[diff]
-        assert np.all(np.abs(vals - kth) <= 4 * rtol * abs(kth)), "selection differs away from the k-th cut"
+        # each of the two indicators is within rtol of the oracle's, so two entries can change
+        # places only when they lie within 2*rtol of each other, i.e. of the k-th value
+        assert np.all(np.abs(vals - kth) <= 2 * rtol * abs(kth)), "selection differs away from the k-th cut"
     return int(diff.size)
 
 

@@ -82,12 +82,12 @@ def test_generation_steps_keep_every_layer_at_its_budget(cake):
                                            np.stack([np.concatenate([r, [0.0]]) for r in gpu_before["ind"]]), S_w, p)[g]
                     lost_gpu = np.setdiff1d(np.arange(n_k + 1), got_idx[g])
                     lost_ref = np.setdiff1d(np.arange(n_k + 1), want["idx"][g])
-                    assert abs(upd[lost_gpu[0]] - upd[lost_ref[0]]) <= 2e-3 * abs(upd[lost_ref[0]]) + 1e-12, full.shape
+                    assert abs(upd[lost_gpu[0]] - upd[lost_ref[0]]) <= 2 * 1e-3 * abs(upd[lost_ref[0]]) + 1e-30, full.shape
                 sel = got_idx[g]
                 k_full = np.concatenate([gpu_before["k"][g], host64(kn[0])[g][None]], axis=0)
                 np.testing.assert_array_equal(host64(cache.k[l][0, g]), co.compact(k_full, sel, S_w))
             assert_close(host64(cache.ind[l][0]), np.stack([want["ind"][g] if np.array_equal(got_idx[g], want["idx"][g])
                                                             else host64(cache.ind[l][0, g]) for g in range(cfg.n_kv_heads)]),
-                         "indicator after the step", rtol=2e-3)
+                         "indicator after the step")
             # the oracle's own trajectory (from its own state) agrees on the indicator values
             oracle_cache[l] = co.decode_step(host64(qn[0]), oracle_cache[l], host64(kn[0]), host64(vn[0]), S_w, p)

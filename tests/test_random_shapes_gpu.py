@@ -51,21 +51,12 @@ def test_random_problem(cake, seed):
     ev = cake.EvictionPass(q, k, v, total, params)
     res = ev.run()
     torch.cuda.synchronize()
-    var_only = pk["indicator_mode"] in (2, 3)
     for l in range(L):
         for b in range(B):
             o = oracle_layer(q[l][b], k[l][b], params)
-            # variance-only indicators cancel in fp32 where the rows agree to many digits: compare
-            # them against the scale of the mean term
-            if var_only:
-                ref = oracle_layer(q[l][b], k[l][b], cake.make_params(**{**pk, "indicator_mode": 1}))["indicator"]
-                scale = ref * ref if pk["indicator_mode"] == 2 else ref ** 3
-                err = np.abs(res.indicator[l][b].double().cpu().numpy() - o["indicator"])
-                assert np.all(err <= 1e-3 * np.abs(o["indicator"]) + 2e-5 * scale + 1e-30), f"indicator l={l} b={b}"
-            else:
-                assert_close(res.indicator[l][b].cpu().numpy(), o["indicator"], f"indicator l={l} b={b}")
+            assert_close(res.indicator[l][b].cpu().numpy(), o["indicator"], f"indicator l={l} b={b}")
             assert_close(res.hv[b, l, 0], o["H"], "H")
-            assert_close(res.hv[b, l, 1], o["V"], "V", rtol=2e-3, atol=1e-12)
+            assert_close(res.hv[b, l, 1], o["V"], "V")
             n_k = int(res.keep[l, b])
             for g in range(h_kv):
                 got = res.idx[l][b, g, :n_k].cpu().numpy()
