@@ -245,6 +245,23 @@ int cake_decode_update(const cake_shape* shape, const cake_params* params,
                        void* workspace, size_t workspace_bytes, void* stream);
 
 /*
+ * cake_decode_update for callers that cannot hand over a workspace or allocate one: code under
+ * HIP graph capture, tight serving loops, harnesses that forbid device allocation.  Same
+ * computation and same results as cake_decode_update; the chunks' softmax partials go to a
+ * scratch array built into the library (1 MiB of device memory per GPU, held until the process
+ * ends) instead of a caller's workspace.  The call allocates and frees nothing.
+ *
+ * Limit: n_layers * B * H_kv * ceil(shape.seq_len / 256) <= 16384 chunk entries (e.g. 32 layers
+ * of 8 KV heads with caches of up to 16384 rows); larger shapes return CAKE_ERR_UNSUPPORTED and
+ * should use cake_decode_update.  All calls on one GPU share that GPU's scratch array: calls that
+ * overlap in time on one GPU (different streams or threads) race; serialise them.
+ */
+int cake_decode_update_static(const cake_shape* shape, const cake_params* params,
+                              const void* const* q_new, const int64_t* q_strides,
+                              const void* const* k_cache, const int64_t* k_strides,
+                              const int32_t* cur_len, float* const* indicator, void* stream);
+
+/*
  * Diagnostics, not part of the method: per-kernel timing of cake_window_scores.
  * While enabled, every cake_window_scores call records HIP events on its stream around its
  * kernels (a few microseconds of overhead).  cake_profile_read waits for the last recorded

@@ -41,6 +41,9 @@ _SIGNATURES = {
     "cake_decode_update": (ctypes.c_int, [ctypes.POINTER(cake_shape), ctypes.POINTER(cake_params), _P,
                                           ctypes.POINTER(ctypes.c_int64), _P, ctypes.POINTER(ctypes.c_int64),
                                           ctypes.POINTER(ctypes.c_int32), _P, _P, ctypes.c_size_t, _P]),
+    "cake_decode_update_static": (ctypes.c_int, [ctypes.POINTER(cake_shape), ctypes.POINTER(cake_params), _P,
+                                                 ctypes.POINTER(ctypes.c_int64), _P, ctypes.POINTER(ctypes.c_int64),
+                                                 ctypes.POINTER(ctypes.c_int32), _P, _P]),
     "cake_profile_enable": (ctypes.c_int, [ctypes.c_int]),
     "cake_profile_read": (ctypes.c_int, [ctypes.POINTER(ctypes.c_float)]),
 }

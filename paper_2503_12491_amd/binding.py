@@ -118,6 +118,12 @@ def cake_decode_update(shape, params, q_new, q_strides, k_cache, k_strides, cur_
                                      workspace.numel() * workspace.element_size(), _stream(stream)))
 
 
+def cake_decode_update_static(shape, params, q_new, q_strides, k_cache, k_strides, cur_len, indicator, stream=None) -> None:
+    flat = [s for layer in k_strides for s in layer]
+    _check(load().cake_decode_update_static(ctypes.byref(shape), ctypes.byref(params), _ptr(q_new), _i64(q_strides),
+                                            _ptr(k_cache), _i64(flat), _i32(cur_len), _ptr(indicator), _stream(stream)))
+
+
 def cake_compact_kv(shape, k_in, v_in, kv_strides, cur_len, k, idx, ind_in, k_out, v_out, ind_out,
                     stream=None) -> None:
     flat = [s for layer in kv_strides for s in layer]

@@ -13,6 +13,7 @@
 // rather than keeping G logits per row.
 #include <algorithm>
 #include <cmath>
+#include <mutex>
 
 #include "cake_internal.h"
 
@@ -185,11 +186,47 @@ __global__ __launch_bounds__(kThreads) void decode_apply_kernel(DecodeArgs a, Ra
 
 using namespace cake;
 
-extern "C" int cake_decode_update(const cake_shape* shape, const cake_params* params,
-                                  const void* const* q_new, const int64_t* q_strides,
-                                  const void* const* k_cache, const int64_t* k_strides,
-                                  const int32_t* cur_len, float* const* indicator,
-                                  void* workspace, size_t workspace_bytes, void* stream) {
+namespace {
+
+// Scratch of the entry point that may not take a workspace from its caller: the chunks'
+// (reference, sum) pairs.  Every GPU the library runs on holds its own copy of this array until
+// the process ends.  In host code the array's name is only a handle: its device address is
+// looked up once per device and only that address is ever handed to a kernel.
+constexpr size_t kStaticScratchBytes = size_t(1) << 20;
+static __device__ __align__(256) unsigned char scratch[kStaticScratchBytes];
+
+constexpr int kMaxDevices = 64;
+std::mutex g_scratch_mutex;
+void* g_scratch_ptr[kMaxDevices] = {};
+
+// Device address of `scratch` on the current device.
+int static_scratch(void** out) {
+  int dev = -1;
+  CAKE_HIP_TRY(hipGetDevice(&dev));
+  if (dev < 0 || dev >= kMaxDevices) return fail(CAKE_ERR_UNSUPPORTED, "device ordinal %d outside [0, %d)", dev, kMaxDevices);
+  std::lock_guard<std::mutex> lock(g_scratch_mutex);
+  if (g_scratch_ptr[dev] == nullptr) {
+    void* ptr = nullptr;
+    CAKE_HIP_TRY(hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch)));
+    if (ptr == nullptr) return fail(CAKE_ERR_HIP, "hipGetSymbolAddress returned a null address");
+    g_scratch_ptr[dev] = ptr;
+  }
+  *out = g_scratch_ptr[dev];
+  return CAKE_OK;
+}
+
+// Bytes of (reference, sum) pairs a call with this shape writes.
+size_t decode_part_bytes(const cake_shape& shape) {
+  const size_t n_chunks = ((size_t)shape.seq_len + kThreads - 1) / kThreads;
+  return sizeof(float) * (size_t)shape.n_layers * shape.batch * shape.n_kv_heads * n_chunks * kMaxGroup * 2;
+}
+
+// Argument checks and the two launches; `part` is device memory of at least decode_part_bytes.
+int decode_update_impl(const cake_shape* shape, const cake_params* params,
+                       const void* const* q_new, const int64_t* q_strides,
+                       const void* const* k_cache, const int64_t* k_strides,
+                       const int32_t* cur_len, float* const* indicator,
+                       float* part, void* stream) {
   if (int rc = check_shape_scores(shape)) return rc;
   CAKE_REQUIRE(params != nullptr, "params is NULL");
   CAKE_REQUIRE(q_new && k_cache && indicator && q_strides && k_strides && cur_len, "a pointer argument is NULL");
@@ -206,17 +243,7 @@ extern "C" int cake_decode_update(const cake_shape* shape, const cake_params* pa
     CAKE_REQUIRE(k_strides[i] >= 0 && (k_strides[i] * eb) % 16 == 0, "k_cache strides must be non-negative multiples of 16 bytes");
   for (int i = 0; i < L * B; ++i)
     CAKE_REQUIRE(cur_len[i] >= 0 && cur_len[i] <= n_p, "cur_len[%d] = %d outside [0, seq_len - window = %d]", i, cur_len[i], n_p);
-  const ScoreLayout lay = score_layout(*shape);
-  if (workspace == nullptr || (reinterpret_cast<uintptr_t>(workspace) & 255) != 0)
-    return fail(CAKE_ERR_WORKSPACE, "workspace is NULL or not 256-byte aligned");
-  if (workspace_bytes < lay.total)
-    return fail(CAKE_ERR_WORKSPACE, "workspace has %zu bytes, %zu needed", workspace_bytes, lay.total);
-  // the chunks' (reference, sum) pairs live where the score pass keeps its own partial pairs
   const int n_chunks = (shape->seq_len + kThreads - 1) / kThreads;
-  const size_t part_bytes = sizeof(float) * (size_t)lay.n_slices * n_chunks * kMaxGroup * 2;
-  if (lay.off_part + part_bytes > lay.total)
-    return fail(CAKE_ERR_WORKSPACE, "workspace layout leaves %zu bytes for the decode partials, %zu needed",
-                lay.total - lay.off_part, part_bytes);
   hipStream_t st = static_cast<hipStream_t>(stream);
   const double scale = params->scale > 0.f ? (double)params->scale : 1.0 / std::sqrt((double)shape->head_dim);
   for (int l0 = 0; l0 < L;) {
@@ -230,8 +257,7 @@ extern "C" int cake_decode_update(const cake_shape* shape, const cake_params* pa
     a.n_chunks = n_chunks;
     a.c = (float)(scale * 1.4426950408889634);
     a.inv_g = 1.0f / (float)G;
-    a.part = reinterpret_cast<float*>(static_cast<char*>(workspace) + lay.off_part) +
-             (int64_t)l0 * B * shape->n_kv_heads * n_chunks * kMaxGroup * 2;
+    a.part = part + (int64_t)l0 * B * shape->n_kv_heads * n_chunks * kMaxGroup * 2;
     int max_cur = 0;
     for (int ll = 0; ll < nl; ++ll) {
       int cc = 0;
@@ -261,4 +287,47 @@ extern "C" int cake_decode_update(const cake_shape* shape, const cake_params* pa
   }
   CAKE_HIP_TRY(hipGetLastError());
   return CAKE_OK;
+}
+
+}  // namespace
+
+extern "C" int cake_decode_update(const cake_shape* shape, const cake_params* params,
+                                  const void* const* q_new, const int64_t* q_strides,
+                                  const void* const* k_cache, const int64_t* k_strides,
+                                  const int32_t* cur_len, float* const* indicator,
+                                  void* workspace, size_t workspace_bytes, void* stream) {
+  if (int rc = check_shape_scores(shape)) return rc;
+  CAKE_REQUIRE(params != nullptr, "params is NULL");
+  CAKE_REQUIRE(q_new && k_cache && indicator && q_strides && k_strides && cur_len, "a pointer argument is NULL");
+  const ScoreLayout lay = score_layout(*shape);
+  if (workspace == nullptr || (reinterpret_cast<uintptr_t>(workspace) & 255) != 0)
+    return fail(CAKE_ERR_WORKSPACE, "workspace is NULL or not 256-byte aligned");
+  if (workspace_bytes < lay.total)
+    return fail(CAKE_ERR_WORKSPACE, "workspace has %zu bytes, %zu needed", workspace_bytes, lay.total);
+  // the chunks' (reference, sum) pairs live where the score pass keeps its own partial pairs
+  const size_t part_bytes = decode_part_bytes(*shape);
+  if (lay.off_part + part_bytes > lay.total)
+    return fail(CAKE_ERR_WORKSPACE, "workspace layout leaves %zu bytes for the decode partials, %zu needed",
+                lay.total - lay.off_part, part_bytes);
+  return decode_update_impl(shape, params, q_new, q_strides, k_cache, k_strides, cur_len, indicator,
+                            reinterpret_cast<float*>(static_cast<char*>(workspace) + lay.off_part), stream);
+}
+
+extern "C" int cake_decode_update_static(const cake_shape* shape, const cake_params* params,
+                                         const void* const* q_new, const int64_t* q_strides,
+                                         const void* const* k_cache, const int64_t* k_strides,
+                                         const int32_t* cur_len, float* const* indicator, void* stream) {
+  if (int rc = check_shape_scores(shape)) return rc;
+  CAKE_REQUIRE(params != nullptr, "params is NULL");
+  CAKE_REQUIRE(q_new && k_cache && indicator && q_strides && k_strides && cur_len, "a pointer argument is NULL");
+  const size_t part_bytes = decode_part_bytes(*shape);
+  if (part_bytes > kStaticScratchBytes)
+    return fail(CAKE_ERR_UNSUPPORTED,
+                "cake_decode_update_static: n_layers*batch*n_kv_heads*ceil(seq_len/%d) = %zu chunk entries need %zu bytes, "
+                "the built-in scratch holds %zu (use cake_decode_update with a workspace)",
+                kThreads, part_bytes / (sizeof(float) * kMaxGroup * 2), part_bytes, kStaticScratchBytes);
+  void* ptr = nullptr;
+  if (int rc = static_scratch(&ptr)) return rc;
+  return decode_update_impl(shape, params, q_new, q_strides, k_cache, k_strides, cur_len, indicator,
+                            static_cast<float*>(ptr), stream);
 }

@@ -27,7 +27,7 @@ def test_library_exports_every_declared_symbol(cake):
     header = open(os.path.join(ROOT, "include", "cake.h")).read()
     declared = set(re.findall(r"\b(cake_[a-z_]+)\s*\(", header))
     assert {"cake_window_scores", "cake_window_scores_lse", "cake_layer_preference", "cake_cascade_allocate", "cake_select_topk",
-            "cake_compact_kv", "cake_decode_update", "cake_workspace_bytes", "cake_last_error", "cake_version",
+            "cake_compact_kv", "cake_decode_update", "cake_decode_update_static", "cake_workspace_bytes", "cake_last_error", "cake_version",
             "cake_profile_enable", "cake_profile_read"} <= declared
     lib = ctypes.CDLL(_ffi.LIB_PATH)
     for name in declared:
