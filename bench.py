@@ -2,8 +2,8 @@
 """Benchmark of the CAKE prefill eviction pass on one MI355X.
 
 One "step" is the whole hot path over one prompt's resident K/V: window scores for all
-layers, layer preferences, the device-to-host hop of the preferences, Eq. 7 allocation on
-the host, per-head top-k and K/V compaction for all layers.  Inputs are synthetic
+layers, layer preferences, Eq. 7 allocation and output placement on the device, per-head
+top-k and K/V compaction for all layers; nothing inside a step waits for the GPU.  Inputs are synthetic
 (synth/generate.py) and already resident in HBM when the timed region starts.
 
 Prints ONE JSON line.  `value` = B*N*L / seconds per step (prefix tokens x layers per second).
@@ -22,11 +22,6 @@ sys.path.insert(0, ROOT)
 HBM_PEAK_GBPS = 8000.0          # MI355X HBM3E
 MFMA_BF16_PEAK_TFLOPS = 2500.0  # dense bf16
 MFMA_F32_PEAK_TFLOPS = 157.3
-VALU_F32_PEAK_TFLOPS = 157.3    # published fp32 vector peak: 256 CUs x 4 SIMDs x one 64-lane FMA per 2 cycles x 2.4 GHz
-# Full-rate vector-ALU issue slots per logit that the arithmetic itself needs.  A slot is one
-# wave-wide fp32 instruction at full rate (2 cycles, 64 lanes x 2 flop); v_exp_f32 runs at a quarter
-# of that rate and counts as four.  Pass 1: fma, exp, add = 6; pass 2: fma, exp, add, fma, fma = 8.
-VALU_SLOTS_PER_LOGIT = {"scores_pass1": 6, "scores_pass2": 8}
 
 
 def parse_args():
@@ -42,6 +37,11 @@ def parse_args():
                          "as a prefill attention kernel would; the scores then read K once")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also run a plain 1 GiB device copy four times (reference for the HBM byte counters)")
+    ap.add_argument("--flush-cache", action="store_true",
+                    help="overwrite a 1 GiB buffer before every step (outside the per-step event bracket), so that small "
+                         "configs start every pass with cold L2 and last-level cache; adds ms_per_step_flushed")
+    ap.add_argument("--host-allocation", action="store_true",
+                    help="variant: budgets on the host (cake_cascade_allocate) between the scores and EVICT")
     return ap.parse_args()
 
 
@@ -163,50 +163,76 @@ def main():
     torch.cuda.synchronize()
 
     # ---- timed region: exactly `steps` passes, per-kernel HIP events on the launch stream ----
+    # (libcake is handed torch's current stream, so torch events and the library's own profiling
+    # events all sit on the stream the kernels run on)
     cake.cake_profile_enable(True)
     first = "scores_pass1" if not args.row_lse else "scores_import_lse"
-    names = [first, "scores_combine", "scores_pass2", "pool_indicator", "layer_preference",
-             "select_topk", "compact_kv"]
+    score_names = [first, "scores_combine", "scores_pass2", "pool_indicator"]
+    names = score_names + ["layer_preference", "plan_eviction", "select_topk+compact_kv"]
+    if args.host_allocation:
+        names = score_names + ["layer_preference", "select_topk", "compact_kv"]
     kernel_ms = {n: 0.0 for n in names}
-    e = [[torch.cuda.Event(enable_timing=True) for _ in range(5)] for _ in range(args.steps)]
-    torch.cuda.synchronize()
-    t_start = time.perf_counter()
+    ne = 6
+    e = [[torch.cuda.Event(enable_timing=True) for _ in range(ne)] for _ in range(args.steps)]
+    flush_buf = torch.empty(1 << 30, dtype=torch.uint8, device=dev) if args.flush_cache else None
     q_str = [q_all[0].stride(i) for i in range(3)]
     k_str = [k_all[0].stride(i) for i in range(3)]
+    keep = None
+    torch.cuda.synchronize()
+    t_start = time.perf_counter()
     for s in range(args.steps):
+        if flush_buf is not None:
+            flush_buf.fill_(s & 0xFF)
+        e[s][0].record()
         if row_lse is None:
             cake.cake_window_scores(ev.shape, ev.params, ev.tbl_q, ev.tbl_k, q_str, k_str, ev.tbl_ind, ev.workspace)
         else:
             cake.cake_window_scores_lse(ev.shape, ev.params, ev.tbl_q, ev.tbl_k, q_str, k_str, ev.tbl_lse, ev.tbl_ind,
                                         ev.workspace)
-        e[s][0].record()
-        cake.cake_layer_preference(ev.shape, ev.params, ev.workspace, ev.pref, ev.hv)
         e[s][1].record()
-        pref, hv = ev.preferences_to_host()
-        ms4 = cake.cake_profile_read()           # events already complete: the stream was just synchronised
-        budgets = ev.allocate(pref)
-        keep = np.minimum(np.maximum(budgets - ev.S_w, 0), ev.N_p)
-        ev._carve_outputs(keep)
-        kk = keep.reshape(-1).tolist()
+        cake.cake_layer_preference(ev.shape, ev.params, ev.workspace, ev.pref, ev.hv)
         e[s][2].record()
-        cake.cake_select_topk(ev.shape, ev.tbl_ind, ev._cur_full, kk, ev.tbl_out[0])
-        e[s][3].record()
-        cake.cake_compact_kv(ev.shape, ev.tbl_k, ev.tbl_v, ev._strides_full, ev._cur_full, kk, ev.tbl_out[0], ev.tbl_ind,
-                             ev.tbl_out[1], ev.tbl_out[2], ev.tbl_out[3])
-        e[s][4].record()
-        for n, ms in zip(names[:4], ms4):
-            kernel_ms[n] += ms
+        if args.host_allocation:
+            pref, hv = ev.preferences_to_host()
+            budgets = ev.allocate(pref)
+            keep = np.minimum(np.maximum(budgets - ev.S_w, 0), ev.N_p)
+            ev._carve_outputs(keep)
+            kk = keep.reshape(-1).tolist()
+            e[s][3].record()
+            cake.cake_select_topk(ev.shape, ev.tbl_ind, ev._cur_full, kk, ev.tbl_out[0])
+            e[s][4].record()
+            cake.cake_compact_kv(ev.shape, ev.tbl_k, ev.tbl_v, ev._strides_full, ev._cur_full, kk, ev.tbl_out[0],
+                                 ev.tbl_ind, ev.tbl_out[1], ev.tbl_out[2], ev.tbl_out[3])
+        else:
+            cake.cake_plan_eviction(ev.shape, ev.pref, ev.total_budget, None, ev.pool_idx, ev.pool_k, ev.pool_v,
+                                    ev.pool_ind, ev.plan, ev.status)
+            e[s][3].record()
+            cake.cake_evict_planned(ev.shape, ev.tbl_ind, ev.tbl_k, ev.tbl_v, k_str, ev.plan)
+            e[s][4].record()
+        e[s][5].record()
     torch.cuda.synchronize()
     elapsed = time.perf_counter() - t_start
-    for s in range(args.steps):
-        kernel_ms["layer_preference"] += e[s][0].elapsed_time(e[s][1])
-        kernel_ms["select_topk"] += e[s][2].elapsed_time(e[s][3])
-        kernel_ms["compact_kv"] += e[s][3].elapsed_time(e[s][4])
+    step_ms = np.array([e[s][0].elapsed_time(e[s][5]) for s in range(args.steps)])
+    score_ms = np.array(cake.cake_profile_read())      # averaged by the library over the profiled calls
+    for n, ms in zip(score_names, score_ms):
+        kernel_ms[n] = float(ms)
+    kernel_ms["layer_preference"] = float(np.mean([e[s][1].elapsed_time(e[s][2]) for s in range(args.steps)]))
+    if args.host_allocation:
+        kernel_ms["select_topk"] = float(np.mean([e[s][3].elapsed_time(e[s][4]) for s in range(args.steps)]))
+        kernel_ms["compact_kv"] = float(np.mean([e[s][4].elapsed_time(e[s][5]) for s in range(args.steps)]))
+    else:
+        kernel_ms["plan_eviction"] = float(np.mean([e[s][2].elapsed_time(e[s][3]) for s in range(args.steps)]))
+        kernel_ms["select_topk+compact_kv"] = float(np.mean([e[s][3].elapsed_time(e[s][4]) for s in range(args.steps)]))
+        budgets, keep, _, _ = ev.read_plan()
     cake.cake_profile_enable(False)
-    kernel_ms = {n: v / args.steps for n, v in kernel_ms.items()}
-    ms_per_step = elapsed / args.steps * 1e3
+    if flush_buf is not None:
+        # the wall clock contains the flushes: the per-step figure is the mean of the event brackets
+        ms_per_step = float(step_ms.mean())
+    else:
+        ms_per_step = elapsed / args.steps * 1e3
+    step_s = ms_per_step * 1e-3
     tokens_layers = B * cfg.seq_len * L
-    value = tokens_layers / (elapsed / args.steps)
+    value = tokens_layers / step_s
 
     # ---- algorithmic bytes (one read of K, indicator traffic, gathered rows) --------------------
     eb = 2 if cfg.dtype == "bf16" else 4
@@ -216,37 +242,35 @@ def main():
     kept_rows = int((keep.sum() + L * B * cfg.window) * cfg.n_kv_heads)
     compact_bytes = kept_rows * cfg.head_dim * eb * 2 * 2                            # K and V, read + write
     alg = {"scores_pass1": k_bytes, "scores_import_lse": 0, "scores_pass2": k_bytes + ind_bytes, "pool_indicator": 2 * ind_bytes,
-           "select_topk": 4 * ind_bytes, "compact_kv": compact_bytes, "scores_combine": 0, "layer_preference": 0}
+           "select_topk": 4 * ind_bytes, "compact_kv": compact_bytes, "select_topk+compact_kv": 4 * ind_bytes + compact_bytes,
+           "scores_combine": 0, "layer_preference": 0, "plan_eviction": 0}
     pass_alg_bytes = k_bytes + ind_bytes * 7 + compact_bytes        # K counted once: the second read is the method's choice
     dominant = max(kernel_ms, key=kernel_ms.get)
     dom_s = kernel_ms[dominant] * 1e-3
-    group = cfg.n_q_heads // cfg.n_kv_heads
     flops_pass = 2.0 * tokens_layers * cfg.n_q_heads * cfg.window * cfg.head_dim   # one logits pass
-    achieved = alg[dominant] / dom_s / 1e9
-    hbm_view = {"achieved": achieved, "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBPS}
-    if dominant in VALU_SLOTS_PER_LOGIT:
-        # The score passes are bound by vector-ALU issue, not by HBM: per key they need G*S_w
-        # exponentials and 3-4 more vector instructions per logit next to the MFMAs.
-        # achieved = logits x slots x 2 flop / time: the flop-equivalents of the minimal
-        # instruction mix (the MFMA work, which shares the SIMD's issue, is not credited; its
-        # rate is in stages.score_mfma_frac).
-        logits = tokens_layers * cfg.n_q_heads * cfg.window
-        tflops = logits * VALU_SLOTS_PER_LOGIT[dominant] * 2.0 / dom_s / 1e12
-        roofline = {"kernel": dominant, "bound": "alu", "achieved": tflops, "peak": VALU_F32_PEAK_TFLOPS,
-                    "unit": "TFLOP/s", "frac": tflops / VALU_F32_PEAK_TFLOPS,
-                    "traffic": measured_traffic(cfg, dominant), "hbm": hbm_view}
-    else:
-        roofline = {"kernel": dominant, "bound": "hbm", **hbm_view, "traffic": measured_traffic(cfg, dominant)}
     mfma_peak = MFMA_BF16_PEAK_TFLOPS if cfg.dtype == "bf16" else MFMA_F32_PEAK_TFLOPS
+    achieved = alg[dominant] / dom_s / 1e9
+    # The dominant kernel streams K once: its algorithmic bytes over its live duration against the
+    # HBM peak.  Its contraction is quoted beside it against the dense MFMA peak of its dtype.
+    roofline = {"kernel": dominant, "bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBPS, "unit": "GB/s",
+                "frac": achieved / HBM_PEAK_GBPS, "traffic": measured_traffic(cfg, dominant),
+                "duration_ms": kernel_ms[dominant]}
+    if dominant in ("scores_pass1", "scores_pass2"):
+        tf = flops_pass / dom_s / 1e12
+        roofline["mfma"] = {"achieved": tf, "peak": mfma_peak, "unit": "TFLOP/s", "frac": tf / mfma_peak}
     score_passes = [n for n in ("scores_pass1", "scores_pass2") if n in kernel_ms]
     extra = {
         "kernel_ms": {n: round(v, 4) for n, v in kernel_ms.items()},
-        "pass_algorithmic_GBps": pass_alg_bytes / (elapsed / args.steps) / 1e9,
-        "pass_hbm_frac": pass_alg_bytes / (elapsed / args.steps) / 1e9 / HBM_PEAK_GBPS,
+        "ms_per_step_median": float(np.median(step_ms)), "ms_per_step_min": float(step_ms.min()),
+        "ms_per_step_event_mean": float(step_ms.mean()),
+        "pass_algorithmic_GBps": pass_alg_bytes / step_s / 1e9,
+        "pass_hbm_frac": pass_alg_bytes / step_s / 1e9 / HBM_PEAK_GBPS,
         "score_mfma_TFLOPs": {n: flops_pass / (kernel_ms[n] * 1e-3) / 1e12 for n in score_passes},
         "score_mfma_frac": {n: flops_pass / (kernel_ms[n] * 1e-3) / 1e12 / mfma_peak for n in score_passes},
-        "host_and_gaps_ms": ms_per_step - sum(kernel_ms.values()),
+        "host_and_gaps_ms": float(step_ms.mean()) - sum(kernel_ms.values()),
     }
+    if flush_buf is not None:
+        extra["ms_per_step_flushed"] = float(step_ms.mean())
 
     out = {
         "metric": "prefix tokens*layers/s evicted at 128K ctx" if cfg.cid == 4 else f"prefix tokens*layers/s evicted (config {cfg.cid})",
@@ -255,7 +279,9 @@ def main():
         "dtype": cfg.dtype, "data": "synthetic",
         "config": {"workload": f"config {cfg.cid} ({cfg.name}): L={L} H_q={cfg.n_q_heads} H_kv={cfg.n_kv_heads} "
                                f"d={cfg.head_dim} N={cfg.seq_len} S_w={cfg.window} B={B} B_total={cfg.total_budget} "
-                               f"one-shot pass" + (", row LSE handed over (K read once)" if args.row_lse else ""), "gamma": params.gamma, "tau1": params.tau1, "tau2": params.tau2,
+                               f"one-shot pass" + (", row LSE handed over (K read once)" if args.row_lse else "")
+                               + (", budgets on the host" if args.host_allocation else "")
+                               + (", caches flushed before every step" if args.flush_cache else ""), "gamma": params.gamma, "tau1": params.tau1, "tau2": params.tau2,
                    "pool_kernel": params.pool_kernel},
         "roofline": roofline, "stages": extra,
     }

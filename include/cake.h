@@ -216,6 +216,42 @@ int cake_compact_kv(const cake_shape* shape,
                     void* stream);
 
 /*
+ * The allocation step and EVICT of a one-shot pass without a host round trip in between.
+ *
+ * cake_plan_eviction computes on the device, for every sequence, the same integer budgets as
+ * cake_cascade_allocate at n_seen = n_layers (Sec. 4.1 Eq. 7; bit-identical to the host routine
+ * on the same preferences), the retained prefix counts k = clamp(B_l - S_w, 0, cur_len) (the
+ * window tokens carry Omega in Sec. 4.3 Eq. 11 and count towards B_l), and the place of every
+ * layer's outputs, one layer after the other, in four caller-owned pools.  All of it is left in
+ * `plan`, device memory of cake_plan_bytes(shape) bytes laid out as
+ *   int32 budgets[L*B], keep[L*B], cur_len[L*B] (entry l*B + b), cap_keep[L], cap_cur[L]
+ *   (cap = maximum over the batch), then from the next multiple of 8 bytes four tables of L
+ *   device pointers: idx, k_out, v_out, ind_out;
+ * the host may copy it back at any later time to learn the budgets.
+ * cake_evict_planned then runs cake_select_topk and cake_compact_kv for all layers with the
+ * counts and output addresses taken from the plan (results identical to those two calls).
+ *
+ *   pref      device [B, n_layers] f64 as written by cake_layer_preference
+ *   cur_len   device [n_layers*B] current evictable lengths, or NULL for N_p = seq_len - window
+ *   pool_idx  device, 16-byte aligned: layer l holds [B, H_kv, cap_keep[l]] int32
+ *   pool_k/v  device: layer l holds [B, H_kv, cap_keep[l] + S_w, d]
+ *   pool_ind  device: layer l holds [B, H_kv, cap_keep[l]] f32
+ *             (sum_l cap_keep[l] <= B*(total_budget - n_layers*S_w) rows bound the pool sizes)
+ *   status    device [B] int32, written: 1 if a preference of the sequence is NaN, negative or
+ *             infinite (the plan then holds the budgets of equal preferences), else 0
+ *   k_in, v_in, indicator, kv_strides  as in cake_compact_kv / cake_select_topk, with one set of
+ *             strides (host [3]) for all layers
+ */
+int cake_plan_bytes(const cake_shape* shape, size_t* bytes /* host, out */);
+int cake_plan_eviction(const cake_shape* shape, const double* pref, int64_t total_budget,
+                       const int32_t* cur_len,
+                       void* pool_idx, void* pool_k, void* pool_v, void* pool_ind,
+                       void* plan, size_t plan_bytes, int32_t* status, void* stream);
+int cake_evict_planned(const cake_shape* shape, const float* const* indicator,
+                       const void* const* k_in, const void* const* v_in, const int64_t* kv_strides,
+                       const void* plan, size_t plan_bytes, void* stream);
+
+/*
  * Indicator maintenance for one generated token (implementation appendix, decoding branch of
  * the listing: the new query's attention over the cached keys outside the window is pooled and
  * the stored indicator is updated with it; Sec. 5, implementation details: eviction also runs
@@ -265,9 +301,10 @@ int cake_decode_update_static(const cake_shape* shape, const cake_params* params
  * Diagnostics, not part of the method: per-kernel timing of cake_window_scores.
  * While enabled, every cake_window_scores call records HIP events on its stream around its
  * kernels (a few microseconds of overhead).  cake_profile_read waits for the last recorded
- * event and returns milliseconds of the most recent call: ms[0] pass 1 (row normalisers),
- * ms[1] combine, ms[2] pass 2 (column statistics), ms[3] pooling.  Process-wide state, not
- * thread-safe; events are created on first use and destroyed by cake_profile_enable(0).
+ * event and returns milliseconds averaged over the calls since cake_profile_enable(1) (at most
+ * the 64 most recent): ms[0] pass 1 (row normalisers), ms[1] combine, ms[2] pass 2 (column
+ * statistics), ms[3] pooling.  Process-wide state, not thread-safe; events are created by
+ * cake_profile_enable(1) and destroyed by cake_profile_enable(0).
  */
 int cake_profile_enable(int enable);
 int cake_profile_read(float* ms /* host [4], out */);

@@ -110,6 +110,36 @@ def cake_select_topk(shape, indicator, cur_len, k, idx, workspace=None, stream=N
                                    _ptr(workspace), ws_bytes, _stream(stream)))
 
 
+def cake_plan_bytes(shape: cake_shape) -> int:
+    out = ctypes.c_size_t(0)
+    _check(load().cake_plan_bytes(ctypes.byref(shape), ctypes.byref(out)))
+    return out.value
+
+
+def cake_plan_eviction(shape, pref, total_budget, cur_len, pool_idx, pool_k, pool_v, pool_ind, plan, status,
+                       stream=None) -> None:
+    _check(load().cake_plan_eviction(ctypes.byref(shape), _ptr(pref), int(total_budget), _ptr(cur_len), _ptr(pool_idx),
+                                     _ptr(pool_k), _ptr(pool_v), _ptr(pool_ind), _ptr(plan),
+                                     plan.numel() * plan.element_size(), _ptr(status), _stream(stream)))
+
+
+def cake_evict_planned(shape, indicator, k_in, v_in, kv_strides, plan, stream=None) -> None:
+    _check(load().cake_evict_planned(ctypes.byref(shape), _ptr(indicator), _ptr(k_in), _ptr(v_in), _i64(kv_strides),
+                                     _ptr(plan), plan.numel() * plan.element_size(), _stream(stream)))
+
+
+def plan_fields(plan_host, n_layers: int, batch: int):
+    """budgets, keep, cur_len [L, B] and cap_keep [L] of a plan copied to the host (a uint8 tensor)."""
+    import numpy as np
+    raw = plan_host.numpy().view(np.int32)
+    lb = n_layers * batch
+    budgets = raw[0:lb].reshape(n_layers, batch)
+    keep = raw[lb:2 * lb].reshape(n_layers, batch)
+    cur = raw[2 * lb:3 * lb].reshape(n_layers, batch)
+    cap_keep = raw[3 * lb:3 * lb + n_layers]
+    return budgets.astype(np.int64), keep.astype(np.int64), cur.astype(np.int64), cap_keep.astype(np.int64)
+
+
 def cake_decode_update(shape, params, q_new, q_strides, k_cache, k_strides, cur_len, indicator, workspace,
                        stream=None) -> None:
     flat = [s for layer in k_strides for s in layer]
@@ -137,8 +167,8 @@ def cake_profile_enable(enable: bool) -> None:
 
 
 def cake_profile_read() -> list:
-    """Milliseconds of the last cake_window_scores call: [pass 1, combine, pass 2, pooling]
-    (with handed-over normalisers: [their import, 0, pass 2, pooling])."""
+    """Milliseconds per cake_window_scores call, averaged over the calls since profiling was enabled:
+    [pass 1, combine, pass 2, pooling] (with handed-over normalisers: [their import, 0, pass 2, pooling])."""
     out = (ctypes.c_float * 4)()
     _check(load().cake_profile_read(out))
     return list(out)

@@ -12,7 +12,7 @@ CSRC = os.path.join(PKG, "csrc")
 OBJ_DIR = os.path.join(ROOT, "_build")
 LIB_PATH = os.path.join(PKG, "libcake.so")
 
-SOURCES = ["cake_host.cpp", "window_scores.hip", "select_topk.hip", "compact_kv.hip", "decode_update.hip"]
+SOURCES = ["cake_host.cpp", "window_scores.hip", "select_topk.hip", "compact_kv.hip", "decode_update.hip", "plan_evict.hip"]
 
 COMMON = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC",

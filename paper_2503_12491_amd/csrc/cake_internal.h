@@ -63,6 +63,49 @@ struct LayerStrides {
   int64_t s[kMaxLaunchLayers][3];
 };
 
+// ---- device-resident eviction plan (cake_plan_eviction writes it, cake_evict_planned reads it) ----
+// int32 budgets[L*B], keep[L*B], cur_len[L*B], cap_keep[L], cap_cur[L]; then, 8-byte aligned,
+// four tables of L device pointers: idx, k_out, v_out, ind_out.
+struct PlanLayout {
+  size_t off_budgets, off_keep, off_cur, off_cap_keep, off_cap_cur, off_tables, total;
+};
+inline PlanLayout plan_layout(int n_layers, int batch) {
+  PlanLayout p{};
+  const size_t lb = (size_t)n_layers * batch * sizeof(int32_t), l4 = (size_t)n_layers * sizeof(int32_t);
+  size_t off = 0;
+  p.off_budgets = off;  off += lb;
+  p.off_keep = off;     off += lb;
+  p.off_cur = off;      off += lb;
+  p.off_cap_keep = off; off += l4;
+  p.off_cap_cur = off;  off += l4;
+  off = align_up(off, 8);
+  p.off_tables = off;   off += 4 * (size_t)n_layers * sizeof(void*);
+  p.total = align_up(off, 256);
+  return p;
+}
+struct PlanView {               // device addresses inside a plan buffer
+  const int32_t* keep;
+  const int32_t* cur_len;
+  const int32_t* cap_keep;
+  const int32_t* cap_cur;
+  void* const* idx;
+  void* const* k_out;
+  void* const* v_out;
+  void* const* ind_out;
+};
+inline PlanView plan_view(const void* plan, int n_layers, int batch) {
+  const PlanLayout lay = plan_layout(n_layers, batch);
+  const char* b = static_cast<const char*>(plan);
+  void* const* t = reinterpret_cast<void* const*>(b + lay.off_tables);
+  return PlanView{reinterpret_cast<const int32_t*>(b + lay.off_keep), reinterpret_cast<const int32_t*>(b + lay.off_cur),
+                  reinterpret_cast<const int32_t*>(b + lay.off_cap_keep), reinterpret_cast<const int32_t*>(b + lay.off_cap_cur),
+                  t, t + n_layers, t + 2 * n_layers, t + 3 * n_layers};
+}
+// top-k and compaction of all layers with the counts and output places read from a plan
+int launch_topk_planned(const cake_shape* shape, const float* const* indicator, const PlanView& plan, hipStream_t stream);
+int launch_compact_planned(const cake_shape* shape, const void* const* k_in, const void* const* v_in,
+                           const int64_t* kv_strides, const float* const* ind_in, const PlanView& plan, hipStream_t stream);
+
 // Layers [l0, l0+nl) that fit one launch under the two limits above.
 inline int launch_layers(int n_layers_left, int batch) {
   int by_entries = kMaxLaunchEntries / batch;

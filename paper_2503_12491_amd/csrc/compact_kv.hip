@@ -26,26 +26,44 @@ struct CompactArgs {
   int32_t cap_keep[kMaxLaunchLayers];
 };
 
-__global__ __launch_bounds__(kThreads) void compact_kernel(CompactArgs a, RaggedDims dims, LayerStrides st) {
+// The same dimensions when they live in device memory (an eviction plan); the strides are then
+// the same for every layer.
+struct CompactPlan {
+  const int32_t* cur_len;     // [L*B]
+  const int32_t* keep;        // [L*B]
+  const int32_t* cap_cur;     // [L]
+  const int32_t* cap_keep;    // [L]
+  int64_t s[3];
+};
+
+// A workgroup moves kThreads*kUnroll pieces at a time and strides over its (layer, sequence, head)
+// slice by the grid's x extent: launches that know the row counts cover a slice in one step,
+// planned launches (counts known only on the device) use a fixed extent.
+template <bool kPlanned>
+__global__ __launch_bounds__(kThreads) void compact_kernel(CompactArgs a, RaggedDims dims, LayerStrides st, CompactPlan plan) {
   const int ll = blockIdx.z;
   const int b = blockIdx.y / a.h_kv, h = blockIdx.y % a.h_kv;
-  const int cur = dims.cur_len[ll * a.batch + b];
-  const int keep = dims.keep[ll * a.batch + b];
+  const int cur = kPlanned ? plan.cur_len[ll * a.batch + b] : dims.cur_len[ll * a.batch + b];
+  const int keep = kPlanned ? plan.keep[ll * a.batch + b] : dims.keep[ll * a.batch + b];
+  const int cap_cur = kPlanned ? plan.cap_cur[ll] : a.cap_cur[ll];
+  const int cap_keep = kPlanned ? plan.cap_keep[ll] : a.cap_keep[ll];
+  const int64_t s0 = kPlanned ? plan.s[0] : st.s[ll][0], s1 = kPlanned ? plan.s[1] : st.s[ll][1],
+                s2 = kPlanned ? plan.s[2] : st.s[ll][2];
   const int rows_out = keep + a.window;
   const int64_t total = (int64_t)rows_out * a.pieces;
-  const int64_t first = (int64_t)blockIdx.x * (kThreads * kUnroll);
-  if (first >= total) return;
 
-  const int64_t in_off = (b * st.s[ll][0] + h * st.s[ll][1]) * a.elem_bytes;
-  const int64_t in_row = st.s[ll][2] * a.elem_bytes;
+  const int64_t in_off = (b * s0 + h * s1) * a.elem_bytes;
+  const int64_t in_row = s2 * a.elem_bytes;
   const int64_t out_row = (int64_t)a.pieces * 16;
-  const int64_t out_off = ((int64_t)b * a.h_kv + h) * (a.cap_keep[ll] + a.window) * out_row;
+  const int64_t out_off = ((int64_t)b * a.h_kv + h) * (cap_keep + a.window) * out_row;
   const char* kin = static_cast<const char*>(a.k_in[ll]) + in_off;
   const char* vin = static_cast<const char*>(a.v_in[ll]) + in_off;
   char* kout = static_cast<char*>(a.k_out[ll]) + out_off;
   char* vout = static_cast<char*>(a.v_out[ll]) + out_off;
-  const int32_t* idx = a.idx[ll] + ((int64_t)b * a.h_kv + h) * a.cap_keep[ll];
+  const int32_t* idx = a.idx[ll] + ((int64_t)b * a.h_kv + h) * cap_keep;
 
+  for (int64_t first = (int64_t)blockIdx.x * (kThreads * kUnroll); first < total;
+       first += (int64_t)gridDim.x * (kThreads * kUnroll)) {
   uint4 kv[kUnroll], vv[kUnroll];
   int64_t dst[kUnroll];
 #pragma unroll
@@ -71,18 +89,40 @@ __global__ __launch_bounds__(kThreads) void compact_kernel(CompactArgs a, Ragged
 
   // indicator entries of the retained prefix positions
   if (a.ind_in != nullptr) {
-    const float* iin = a.ind_in[ll] + ((int64_t)b * a.h_kv + h) * a.cap_cur[ll];
-    float* iout = a.ind_out[ll] + ((int64_t)b * a.h_kv + h) * a.cap_keep[ll];
+    const float* iin = a.ind_in[ll] + ((int64_t)b * a.h_kv + h) * cap_cur;
+    float* iout = a.ind_out[ll] + ((int64_t)b * a.h_kv + h) * cap_keep;
     const int64_t r0 = first / a.pieces;                               // rows this block touches
     const int64_t r1 = min((first + kThreads * kUnroll + a.pieces - 1) / a.pieces, (int64_t)keep);
     // a row split between two blocks is written by the block that holds its piece 0
     for (int64_t r = r0 + threadIdx.x; r < r1; r += kThreads)
       if (r * a.pieces >= first) iout[r] = iin[min(max(idx[r], 0), cur - 1)];
   }
+  }
 }
 
 }  // namespace
 }  // namespace cake
+
+int cake::launch_compact_planned(const cake_shape* shape, const void* const* k_in, const void* const* v_in,
+                                 const int64_t* kv_strides, const float* const* ind_in, const PlanView& plan,
+                                 hipStream_t stream) {
+  const int eb = (int)elem_bytes(shape->dtype);
+  CompactArgs a{};
+  a.k_in = k_in; a.v_in = v_in;
+  a.idx = reinterpret_cast<const int32_t* const*>(plan.idx);
+  a.ind_in = ind_in;
+  a.k_out = plan.k_out; a.v_out = plan.v_out;
+  a.ind_out = ind_in ? reinterpret_cast<float* const*>(plan.ind_out) : nullptr;
+  a.batch = shape->batch; a.h_kv = shape->n_kv_heads; a.window = shape->window;
+  a.pieces = shape->head_dim * eb / 16;
+  a.elem_bytes = eb;
+  CompactPlan cp{plan.cur_len, plan.keep, plan.cap_cur, plan.cap_keep, {kv_strides[0], kv_strides[1], kv_strides[2]}};
+  // 64 workgroups stride over each (layer, sequence, head) slice: one step each up to 4096 rows of 16 pieces
+  hipLaunchKernelGGL(compact_kernel<true>, dim3(64, shape->batch * shape->n_kv_heads, shape->n_layers), dim3(kThreads), 0,
+                     stream, a, RaggedDims{}, LayerStrides{}, cp);
+  CAKE_HIP_TRY(hipGetLastError());
+  return CAKE_OK;
+}
 
 using namespace cake;
 
@@ -137,7 +177,7 @@ extern "C" int cake_compact_kv(const cake_shape* shape,
     }
     const int64_t pieces_total = (int64_t)max_rows * a.pieces;
     const unsigned gx = (unsigned)((pieces_total + kThreads * kUnroll - 1) / (kThreads * kUnroll));
-    hipLaunchKernelGGL(compact_kernel, dim3(gx, B * shape->n_kv_heads, nl), dim3(kThreads), 0, st, a, dims, ls);
+    hipLaunchKernelGGL(compact_kernel<false>, dim3(gx, B * shape->n_kv_heads, nl), dim3(kThreads), 0, st, a, dims, ls, CompactPlan{});
     l0 += nl;
   }
   CAKE_HIP_TRY(hipGetLastError());

@@ -29,6 +29,13 @@ struct TopkArgs {
   int32_t cap_cur[kMaxLaunchLayers];
   int32_t cap_keep[kMaxLaunchLayers];
 };
+// The same dimensions when they live in device memory (an eviction plan).
+struct TopkPlan {
+  const int32_t* cur_len;     // [L*B]
+  const int32_t* keep;        // [L*B]
+  const int32_t* cap_cur;     // [L]
+  const int32_t* cap_keep;    // [L]
+};
 
 // Larger float <=> larger key.  -0 is folded onto +0 first so that they compare equal.
 __device__ __forceinline__ uint32_t order_key(float x) {
@@ -71,19 +78,22 @@ struct Row {
   }
 };
 
-__global__ __launch_bounds__(kThreads) void select_topk_kernel(TopkArgs a, RaggedDims dims) {
+template <bool kPlanned>
+__global__ __launch_bounds__(kThreads) void select_topk_kernel(TopkArgs a, RaggedDims dims, TopkPlan plan) {
   __shared__ __attribute__((aligned(16))) uint32_t hist[kMaxBins * kCopies];     // [digit][copy]
   __shared__ uint32_t sel_prefix, sel_need;
   __shared__ uint32_t wave_tot[2][kWaves];
 
   const int ll = blockIdx.y;                         // layer within this launch
   const int b = blockIdx.x / a.h_kv, h = blockIdx.x % a.h_kv;
-  const int cur = dims.cur_len[ll * a.batch + b];
-  const int keep = dims.keep[ll * a.batch + b];
+  const int cur = kPlanned ? plan.cur_len[ll * a.batch + b] : dims.cur_len[ll * a.batch + b];
+  const int keep = kPlanned ? plan.keep[ll * a.batch + b] : dims.keep[ll * a.batch + b];
   if (keep <= 0) return;
+  const int cap_cur = kPlanned ? plan.cap_cur[ll] : a.cap_cur[ll];
+  const int cap_keep = kPlanned ? plan.cap_keep[ll] : a.cap_keep[ll];
   Row row;
-  row.init(a.indicator[ll] + ((int64_t)b * a.h_kv + h) * a.cap_cur[ll], cur);
-  int32_t* out = a.idx[ll] + ((int64_t)b * a.h_kv + h) * a.cap_keep[ll];
+  row.init(a.indicator[ll] + ((int64_t)b * a.h_kv + h) * cap_cur, cur);
+  int32_t* out = a.idx[ll] + ((int64_t)b * a.h_kv + h) * cap_keep;
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int copy = lane & (kCopies - 1);
 
@@ -245,6 +255,19 @@ __global__ __launch_bounds__(kThreads) void select_topk_kernel(TopkArgs a, Ragge
 }  // namespace
 }  // namespace cake
 
+int cake::launch_topk_planned(const cake_shape* shape, const float* const* indicator, const PlanView& plan, hipStream_t stream) {
+  TopkArgs a{};
+  a.indicator = indicator;
+  a.idx = reinterpret_cast<int32_t* const*>(plan.idx);
+  a.batch = shape->batch;
+  a.h_kv = shape->n_kv_heads;
+  const TopkPlan tp{plan.cur_len, plan.keep, plan.cap_cur, plan.cap_keep};
+  hipLaunchKernelGGL(select_topk_kernel<true>, dim3(shape->batch * shape->n_kv_heads, shape->n_layers), dim3(kThreads), 0,
+                     stream, a, RaggedDims{}, tp);
+  CAKE_HIP_TRY(hipGetLastError());
+  return CAKE_OK;
+}
+
 using namespace cake;
 
 extern "C" int cake_select_topk(const cake_shape* shape, const float* const* indicator,
@@ -283,7 +306,7 @@ extern "C" int cake_select_topk(const cake_shape* shape, const float* const* ind
       any = any || ck > 0;
     }
     if (any)
-      hipLaunchKernelGGL(select_topk_kernel, dim3(B * shape->n_kv_heads, nl), dim3(kThreads), 0, st, a, dims);
+      hipLaunchKernelGGL(select_topk_kernel<false>, dim3(B * shape->n_kv_heads, nl), dim3(kThreads), 0, st, a, dims, TopkPlan{});
     l0 += nl;
   }
   CAKE_HIP_TRY(hipGetLastError());

@@ -312,21 +312,35 @@ __global__ __launch_bounds__(512) void scores_pass1(ScoreArgs a) {
   }
 }
 
-// Combine the chunks' pairs of every window row into lse2 = log2 sum_j 2^(t_j).
-__global__ void scores_combine(ScoreArgs a, int rows_per_slice, int64_t total_rows) {
-  int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
-  if (i >= total_rows) return;
-  int64_t slice = i / rows_per_slice;
-  int row = (int)(i % rows_per_slice);
+// Combine the chunks' pairs of every window row into lse2 = log2 sum_j 2^(t_j).  Four lanes share
+// a row: each folds every fourth chunk into a running (reference, sum) pair in one sweep, the four
+// pairs are merged in a fixed order.
+__global__ __launch_bounds__(256) void scores_combine(ScoreArgs a, int rows_per_slice, int64_t total_rows) {
+  const int64_t i = ((int64_t)blockIdx.x * blockDim.x + threadIdx.x) >> 2;
+  const int part = threadIdx.x & 3;
+  const bool live = i < total_rows;
+  const int64_t slice = live ? i / rows_per_slice : 0;
+  const int row = live ? (int)(i % rows_per_slice) : 0;
   const float* p = a.part + (slice * a.n_chunks * rows_per_slice + row) * 2;
   float m = kMasked;
-  for (int c = 0; c < a.n_chunks; ++c) m = fmaxf(m, p[(int64_t)c * rows_per_slice * 2]);
   double s = 0.0;
-  for (int c = 0; c < a.n_chunks; ++c) {
-    const float* pc = p + (int64_t)c * rows_per_slice * 2;
-    s += (double)pc[1] * (double)exp2f(pc[0] - m);
+  for (int c = part; live && c < a.n_chunks; c += 4) {
+    const float2 pc = *reinterpret_cast<const float2*>(p + (int64_t)c * rows_per_slice * 2);
+    if (pc.x > m) { s *= (double)exp2f(m - pc.x); m = pc.x; }
+    s += (double)pc.y * (double)exp2f(pc.x - m);
   }
-  a.lse[i] = m + (float)log2(s);
+#pragma unroll
+  for (int off = 1; off <= 2; off <<= 1) {
+    const float om = __shfl_xor(m, off);
+    const double os = __shfl_xor(s, off);
+    const float mm = fmaxf(m, om);
+    // the lower lane's pair first: the same order in both partners
+    const double lo_s = (part & off) ? os : s, hi_s = (part & off) ? s : os;
+    const float lo_m = (part & off) ? om : m, hi_m = (part & off) ? m : om;
+    s = lo_s * (double)exp2f(lo_m - mm) + hi_s * (double)exp2f(hi_m - mm);
+    m = mm;
+  }
+  if (live && part == 0) a.lse[i] = m + (float)log2(s);
 }
 
 // Row normalisers handed over by the caller (natural log, [B, H_q, S_w] per layer) -> log2 domain
@@ -627,15 +641,18 @@ __global__ void layer_preference_kernel(const float* hv, int n_layers, int batch
   }
 }
 
-// Optional event timing of the four kernels (diagnostics).
+// Optional event timing of the four kernels (diagnostics).  Process-wide and not thread-safe:
+// one set of five events per profiled call, the last kProfileSets calls are kept.
+constexpr int kProfileSets = 64;
 struct Profile {
-  bool enabled = false, recorded = false, created = false;
-  hipEvent_t ev[5] = {};
+  bool enabled = false, created = false;
+  int64_t calls = 0;                       // profiled calls since cake_profile_enable(1)
+  hipEvent_t ev[kProfileSets][5] = {};
 };
 Profile g_profile;
 
 inline void mark(int i, hipStream_t stream) {
-  if (g_profile.enabled && g_profile.created) (void)hipEventRecord(g_profile.ev[i], stream);
+  if (g_profile.enabled && g_profile.created) (void)hipEventRecord(g_profile.ev[g_profile.calls % kProfileSets][i], stream);
 }
 
 template <typename T, int D, int MB, bool kPivot>
@@ -647,7 +664,7 @@ int launch_scores(const ScoreArgs& a, int64_t n_slices, const float* const* row_
   if (row_lse == nullptr) {
     hipLaunchKernelGGL((scores_pass1<T, D, MB>), dim3(a.n_chunks, (unsigned)n_slices), block, 0, stream, a);
     mark(1, stream);
-    hipLaunchKernelGGL(scores_combine, dim3((unsigned)((total_rows + 255) / 256)), dim3(256), 0, stream, a, rows, total_rows);
+    hipLaunchKernelGGL(scores_combine, dim3((unsigned)((total_rows * 4 + 255) / 256)), dim3(256), 0, stream, a, rows, total_rows);
   } else {
     const int64_t per_layer = (int64_t)a.batch * a.h_kv * rows;
     hipLaunchKernelGGL(scores_import_lse, dim3((unsigned)((total_rows + 255) / 256)), dim3(256), 0, stream, a, row_lse,
@@ -659,7 +676,7 @@ int launch_scores(const ScoreArgs& a, int64_t n_slices, const float* const* row_
   mark(3, stream);
   hipLaunchKernelGGL(pool_indicator, dim3((a.n_p + kPoolSpan - 1) / kPoolSpan, (unsigned)n_slices), dim3(256), 0, stream, a);
   mark(4, stream);
-  if (g_profile.enabled && g_profile.created) g_profile.recorded = true;
+  if (g_profile.enabled && g_profile.created) g_profile.calls += 1;
   CAKE_HIP_TRY(hipGetLastError());
   return CAKE_OK;
 }
@@ -671,23 +688,35 @@ using namespace cake;
 
 extern "C" int cake_profile_enable(int enable) {
   if (enable && !g_profile.created) {
-    for (auto& e : g_profile.ev) CAKE_HIP_TRY(hipEventCreate(&e));
+    for (auto& set : g_profile.ev)
+      for (auto& e : set) CAKE_HIP_TRY(hipEventCreate(&e));
     g_profile.created = true;
   }
   if (!enable && g_profile.created) {
-    for (auto& e : g_profile.ev) (void)hipEventDestroy(e);
+    for (auto& set : g_profile.ev)
+      for (auto& e : set) (void)hipEventDestroy(e);
     g_profile.created = false;
-    g_profile.recorded = false;
   }
+  g_profile.calls = 0;
   g_profile.enabled = enable != 0;
   return CAKE_OK;
 }
 
 extern "C" int cake_profile_read(float* ms) {
   CAKE_REQUIRE(ms != nullptr, "ms is NULL");
-  CAKE_REQUIRE(g_profile.enabled && g_profile.recorded, "no profiled cake_window_scores call to read");
-  CAKE_HIP_TRY(hipEventSynchronize(g_profile.ev[4]));
-  for (int i = 0; i < 4; ++i) CAKE_HIP_TRY(hipEventElapsedTime(&ms[i], g_profile.ev[i], g_profile.ev[i + 1]));
+  CAKE_REQUIRE(g_profile.enabled && g_profile.calls > 0, "no profiled cake_window_scores call to read");
+  const int64_t n = g_profile.calls < kProfileSets ? g_profile.calls : kProfileSets;
+  double sum[4] = {0, 0, 0, 0};
+  for (int64_t c = g_profile.calls - n; c < g_profile.calls; ++c) {
+    hipEvent_t* ev = g_profile.ev[c % kProfileSets];
+    CAKE_HIP_TRY(hipEventSynchronize(ev[4]));
+    for (int i = 0; i < 4; ++i) {
+      float x = 0.f;
+      CAKE_HIP_TRY(hipEventElapsedTime(&x, ev[i], ev[i + 1]));
+      sum[i] += x;
+    }
+  }
+  for (int i = 0; i < 4; ++i) ms[i] = (float)(sum[i] / (double)n);
   return CAKE_OK;
 }
 

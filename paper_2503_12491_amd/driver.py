@@ -1,8 +1,9 @@
 """Stage driver for the eviction pass: sequences the five libcake calls (Alg. 1 / Sec. 4.1).
 
 Orchestration and buffer management only; every computation happens inside libcake.
-One-shot mode (Sec. 4.1): scores for all layers, preferences to the host, Eq. 7 budgets,
-top-k and compaction for all layers.  Cascade mode (Sec. 4.2, Alg. 1): stage m admits layer
+One-shot mode (Sec. 4.1): scores for all layers, Eq. 7 budgets and the placement of the outputs on
+the device (cake_plan_eviction), top-k and compaction for all layers (cake_evict_planned); the host
+reads the plan back once at the end.  Cascade mode (Sec. 4.2, Alg. 1): stage m admits layer
 m, recomputes B^(m) and re-evicts layers 0..m from their already compacted caches.
 """
 from __future__ import annotations
@@ -88,6 +89,11 @@ class EvictionPass:
         self._strides_full = [_strides3(k0)] * self.L
         self.tbl_out_host = torch.empty(4, self.L, dtype=torch.int64).pin_memory()
         self.tbl_out = torch.empty(4, self.L, dtype=torch.int64, device=self.dev)
+        # device-resident plan of the one-shot pass (budgets, keep counts, output places) and its host copy
+        self.plan = torch.empty(C.cake_plan_bytes(self.shape), dtype=torch.uint8, device=self.dev)
+        self.plan_host = torch.empty(self.plan.numel(), dtype=torch.uint8).pin_memory()
+        self.status = torch.empty(self.B, dtype=torch.int32, device=self.dev)
+        self.status_host = torch.empty(self.B, dtype=torch.int32).pin_memory()
 
     # ------------------------------------------------------------------ the five calls
     def scores(self, stream=None) -> None:
@@ -161,21 +167,56 @@ class EvictionPass:
         return (keep,) + self._views(*placement)
 
     # ------------------------------------------------------------------ whole pass
+    def plan_and_evict(self, stream=None) -> None:
+        """Eq. 7 budgets, keep counts and output placement on the device, then top-k and
+        compaction of all layers from that plan.  Nothing here waits for the GPU."""
+        C.cake_plan_eviction(self.shape, self.pref, self.total_budget, None, self.pool_idx, self.pool_k, self.pool_v,
+                             self.pool_ind, self.plan, self.status, stream)
+        C.cake_evict_planned(self.shape, self.tbl_ind, self.tbl_k, self.tbl_v, _strides3(self.k[0]), self.plan, stream)
+
+    def read_plan(self):
+        """Budgets and keep counts [L, B] of the last planned pass, preferences and (H, V): one
+        read-back after the whole pass has been enqueued."""
+        self.plan_host.copy_(self.plan, non_blocking=True)
+        self.status_host.copy_(self.status, non_blocking=True)
+        pref, hv = self.preferences_to_host()           # synchronises the stream
+        if int(self.status_host.max()) != 0:
+            raise C.CakeError(-1, "a layer preference is NaN, negative or infinite")
+        budgets, keep, _, _ = C.plan_fields(self.plan_host, self.L, self.B)
+        return budgets, keep, pref, hv
+
+    def _placement(self, keep: np.ndarray):
+        """Element offsets of every layer's outputs in the pools (the rule cake_plan_eviction applies)."""
+        caps = keep.max(axis=1).astype(np.int64)
+        bh = self.B * self.H_kv
+        n_kv = bh * (caps + self.S_w) * self.d
+        n_i = bh * caps
+        return caps, np.concatenate([[0], np.cumsum(n_kv)[:-1]]), np.concatenate([[0], np.cumsum(n_i)[:-1]])
+
     def run(self) -> PassResult:
-        """One-shot pass (Sec. 4.1): all layers scored, Eq. 7 budgets, one EVICT per layer."""
+        """One-shot pass (Sec. 4.1): all layers scored, Eq. 7 budgets, one EVICT per layer; the host
+        waits once, at the end."""
+        self.scores()
+        self.plan_and_evict()
+        budgets, keep, pref, hv = self.read_plan()
+        idx, k_out, v_out, ind_out = self._views(*self._placement(keep))
+        return PassResult(budgets, keep, pref, hv, [self.indicator[l] for l in range(self.L)], idx, k_out, v_out,
+                          ind_out)
+
+    def run_launch_only(self) -> None:
+        """The same pass, enqueued only (what a serving loop, and bench.py, time)."""
+        self.scores()
+        self.plan_and_evict()
+
+    def run_host_allocated(self) -> PassResult:
+        """The one-shot pass with the allocation on the host (cake_cascade_allocate): preferences read
+        back, budgets computed, counts handed to cake_select_topk / cake_compact_kv as host arrays."""
         self.scores()
         pref, hv = self.preferences_to_host()
         budgets = self.allocate(pref)
         keep, idx, k_out, v_out, ind_out = self.evict(budgets)
         return PassResult(budgets, keep, pref, hv, [self.indicator[l] for l in range(self.L)], idx, k_out, v_out,
                           ind_out)
-
-    def run_launch_only(self):
-        """The same pass without building result views (what a serving loop, and bench.py, time)."""
-        self.scores()
-        pref, hv = self.preferences_to_host()
-        budgets = self.allocate(pref)
-        return self.evict_launch(budgets)
 
     def run_cascade(self, track_positions: bool = True) -> PassResult:
         """Cascading pass (Sec. 4.2, Alg. 1) over the layers this object was built with: every layer
