@@ -281,6 +281,41 @@ int cake_decode_update(const cake_shape* shape, const cake_params* params,
                        void* workspace, size_t workspace_bytes, void* stream);
 
 /*
+ * The same decode-phase maintenance in place: one generated token at each of n_layers layers
+ * (normally one), with K and V touched at a single row per head.
+ *
+ * The cache of a (layer, sequence, KV head) lives in cap + S_w + 1 physical slots that never move.
+ * order[0 .. cur + S_w) lists the slots in logical order: the cur scored rows by position, then
+ * the S_w window rows, oldest first.  The call (1) copies the token's key and value into the free
+ * slot and appends it to the list, which turns the oldest window row into the last scored row,
+ * starting at indicator 0; (2) updates the indicator of the cur + 1 scored rows exactly as
+ * cake_decode_update does (softmax of the G new query rows over all listed rows, group mean,
+ * max-pool along the logical order, added); (3) evicts the scored row with the smallest updated
+ * indicator, the later one among equals, i.e. the row that cake_select_topk at k = cur leaves
+ * out: it is deleted from the list and from the indicator (later entries move down by one) and
+ * its slot becomes the free one.  cur does not change.
+ *
+ *   shape      seq_len >= max over layers of cap + S_w + 1 (sizes the workspace)
+ *   q_new      device [n_layers, B, H_q, d], element strides q_strides (host [3]: layer, batch, head)
+ *   k_new, v_new  device [n_layers, B, H_kv, d], element strides kv_new_strides (host [3])
+ *   k_slots, v_slots  tables; [B, H_kv, cap_l + S_w + 1, d], element strides slot_strides
+ *              (host [3]: batch, head, slot; the same for every layer of the call), updated
+ *   indicator  table; indicator[l] -> [B, H_kv, cap_l + 1] f32 in logical order, updated
+ *   order      table; order[l] -> [B, H_kv, cap_l + S_w + 1] int32, updated
+ *   state      table; state[l] -> [B, H_kv, 4] int32: {cur, free slot, logical index of the row
+ *              evicted by the last call, unused}; the caller sets cur and the free slot once
+ *   cap        host [n_layers]: scored-row capacity cap_l of the layer's arrays (cur <= cap_l)
+ *   workspace  device scratch of at least cake_decode_step_workspace_bytes(shape), 256-byte aligned
+ */
+int cake_decode_step_workspace_bytes(const cake_shape* shape, size_t* bytes /* host, out */);
+int cake_decode_step(const cake_shape* shape, const cake_params* params,
+                     const void* q_new, const int64_t* q_strides,
+                     const void* k_new, const void* v_new, const int64_t* kv_new_strides,
+                     void* const* k_slots, void* const* v_slots, const int64_t* slot_strides,
+                     float* const* indicator, int32_t* const* order, int32_t* const* state,
+                     const int32_t* cap, void* workspace, size_t workspace_bytes, void* stream);
+
+/*
  * cake_decode_update for callers that cannot hand over a workspace or allocate one: code under
  * HIP graph capture, tight serving loops, harnesses that forbid device allocation.  Same
  * computation and same results as cake_decode_update; the chunks' softmax partials go to a

@@ -46,6 +46,11 @@ _SIGNATURES = {
     "cake_decode_update": (ctypes.c_int, [ctypes.POINTER(cake_shape), ctypes.POINTER(cake_params), _P,
                                           ctypes.POINTER(ctypes.c_int64), _P, ctypes.POINTER(ctypes.c_int64),
                                           ctypes.POINTER(ctypes.c_int32), _P, _P, ctypes.c_size_t, _P]),
+    "cake_decode_step_workspace_bytes": (ctypes.c_int, [ctypes.POINTER(cake_shape), ctypes.POINTER(ctypes.c_size_t)]),
+    "cake_decode_step": (ctypes.c_int, [ctypes.POINTER(cake_shape), ctypes.POINTER(cake_params), _P,
+                                        ctypes.POINTER(ctypes.c_int64), _P, _P, ctypes.POINTER(ctypes.c_int64), _P, _P,
+                                        ctypes.POINTER(ctypes.c_int64), _P, _P, _P, ctypes.POINTER(ctypes.c_int32), _P,
+                                        ctypes.c_size_t, _P]),
     "cake_decode_update_static": (ctypes.c_int, [ctypes.POINTER(cake_shape), ctypes.POINTER(cake_params), _P,
                                                  ctypes.POINTER(ctypes.c_int64), _P, ctypes.POINTER(ctypes.c_int64),
                                                  ctypes.POINTER(ctypes.c_int32), _P, _P]),

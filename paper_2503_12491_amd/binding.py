@@ -148,6 +148,20 @@ def cake_decode_update(shape, params, q_new, q_strides, k_cache, k_strides, cur_
                                      workspace.numel() * workspace.element_size(), _stream(stream)))
 
 
+def cake_decode_step_workspace_bytes(shape: cake_shape) -> int:
+    out = ctypes.c_size_t(0)
+    _check(load().cake_decode_step_workspace_bytes(ctypes.byref(shape), ctypes.byref(out)))
+    return out.value
+
+
+def cake_decode_step(shape, params, q_new, q_strides, k_new, v_new, kv_new_strides, k_slots, v_slots, slot_strides,
+                     indicator, order, state, cap, workspace, stream=None) -> None:
+    _check(load().cake_decode_step(ctypes.byref(shape), ctypes.byref(params), _ptr(q_new), _i64(q_strides), _ptr(k_new),
+                                   _ptr(v_new), _i64(kv_new_strides), _ptr(k_slots), _ptr(v_slots), _i64(slot_strides),
+                                   _ptr(indicator), _ptr(order), _ptr(state), _i32(cap), _ptr(workspace),
+                                   workspace.numel() * workspace.element_size(), _stream(stream)))
+
+
 def cake_decode_update_static(shape, params, q_new, q_strides, k_cache, k_strides, cur_len, indicator, stream=None) -> None:
     flat = [s for layer in k_strides for s in layer]
     _check(load().cake_decode_update_static(ctypes.byref(shape), ctypes.byref(params), _ptr(q_new), _i64(q_strides),

@@ -181,6 +181,216 @@ __global__ __launch_bounds__(kThreads) void decode_apply_kernel(DecodeArgs a, Ra
   }
 }
 
+
+// ------------------------------------------------------------------------------------------
+// In-place decode step (cake_decode_step).  The cache of a (layer, sequence, KV head) lives in
+// fixed physical slots; `order` lists the slots in logical order: the cur scored rows by position,
+// then the S_w window rows, oldest first.  One generated token: its key and value go to the free
+// slot and are appended to the list, so the oldest window row becomes the last scored row (with
+// indicator 0); the indicator is updated as in cake_decode_update; the scored row with the
+// smallest indicator (the later one among equals: what top-k at k = cur under (value descending,
+// position ascending) leaves out) is deleted from the list and its slot becomes the free one.
+// K and V are touched at one row per head; only the 4-byte list entries and indicators move.
+// ------------------------------------------------------------------------------------------
+struct StepArgs {
+  const void* q_new; const void* k_new; const void* v_new;
+  void* const* k_slots; void* const* v_slots;
+  float* const* indicator; int32_t* const* order; int32_t* const* state;
+  int64_t qs[3], ns[3], ss[3];      // element strides: q_new / k_new,v_new (layer, batch, head); slots (batch, head, slot)
+  int32_t batch, h_kv, group, window, pool, n_chunks, rows_max;
+  float c, inv_g;
+  float* logits;      // [slice][rows_max][kMaxGroup]
+  float* part;        // [slice][n_chunks][kMaxGroup][2]
+  float* amin;        // [slice][n_chunks][2]: (value, logical index as float bits)
+  int32_t cap[kMaxLaunchLayers];
+};
+
+// Step kernel 1: the new row goes to its slot and onto the list; logits of the G heads for every
+// listed row (kept for the second kernel) and the chunks' (reference, sum) pairs.
+template <typename T, int D>
+__global__ __launch_bounds__(kThreads) void step_logits_kernel(StepArgs a) {
+  __shared__ float q_lds[kMaxGroup * D];
+  __shared__ float red_m[kWaves][kMaxGroup], red_l[kWaves][kMaxGroup];
+  const int chunk = blockIdx.x, ll = blockIdx.z;
+  const int b = blockIdx.y / a.h_kv, g = blockIdx.y % a.h_kv;
+  const int64_t slice = ((int64_t)ll * a.batch + b) * a.h_kv + g;
+  const int32_t* st = a.state[ll] + ((int64_t)b * a.h_kv + g) * 4;
+  const int cur = st[0], free_slot = st[1];
+  const int n = cur + 1 + a.window;                       // rows the new query sees
+  if (chunk * kThreads >= n) return;
+  const int cap = a.cap[ll];
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const T* q = reinterpret_cast<const T*>(a.q_new) + ll * a.qs[0] + b * a.qs[1] + (int64_t)(g * a.group) * a.qs[2];
+  T* ks = reinterpret_cast<T*>(a.k_slots[ll]) + b * a.ss[0] + g * a.ss[1];
+  int32_t* order = a.order[ll] + ((int64_t)b * a.h_kv + g) * (cap + a.window + 1);
+  for (int i = tid; i < a.group * D; i += kThreads) q_lds[i] = (float)q[(i / D) * a.qs[2] + (i % D)];
+  __syncthreads();
+
+  const int j = chunk * kThreads + tid;
+  float m[kMaxGroup], l[kMaxGroup];
+#pragma unroll
+  for (int h = 0; h < kMaxGroup; ++h) { m[h] = kMasked; l[h] = 0.f; }
+  if (j < n) {
+    const T* row;
+    if (j == n - 1) {
+      // the generated token: copy its key and value into the free slot, list it, start its
+      // predecessor in the scored part (the row that just left the window) at indicator 0
+      const T* kn = reinterpret_cast<const T*>(a.k_new) + ll * a.ns[0] + b * a.ns[1] + g * a.ns[2];
+      const T* vn = reinterpret_cast<const T*>(a.v_new) + ll * a.ns[0] + b * a.ns[1] + g * a.ns[2];
+      T* kd = ks + free_slot * a.ss[2];
+      T* vd = reinterpret_cast<T*>(a.v_slots[ll]) + b * a.ss[0] + g * a.ss[1] + free_slot * a.ss[2];
+      for (int e = 0; e < D; e += 16 / (int)sizeof(T)) {
+        *reinterpret_cast<uint4*>(kd + e) = *reinterpret_cast<const uint4*>(kn + e);
+        *reinterpret_cast<uint4*>(vd + e) = *reinterpret_cast<const uint4*>(vn + e);
+      }
+      order[j] = free_slot;
+      a.indicator[ll][((int64_t)b * a.h_kv + g) * (cap + 1) + cur] = 0.f;
+      row = kn;
+    } else {
+      row = ks + order[j] * a.ss[2];
+    }
+    row_logits<T, D>(row, q_lds, a.group, a.c, m);
+    float* lg = a.logits + (slice * a.rows_max + j) * kMaxGroup;
+#pragma unroll
+    for (int h = 0; h < kMaxGroup; ++h) { lg[h] = m[h]; l[h] = 1.f; }
+  }
+#pragma unroll
+  for (int h = 0; h < kMaxGroup; ++h) {
+#pragma unroll
+    for (int off = 32; off >= 1; off >>= 1) {
+      const float om = __shfl_xor(m[h], off), ol = __shfl_xor(l[h], off);
+      const float mn = fmaxf(m[h], om);
+      l[h] = l[h] * exp2f(m[h] - mn) + ol * exp2f(om - mn);
+      m[h] = mn;
+    }
+    if (lane == 0) { red_m[wave][h] = m[h]; red_l[wave][h] = l[h]; }
+  }
+  __syncthreads();
+  if (tid < a.group) {
+    float mm = kMasked, sum = 0.f;
+    for (int w = 0; w < kWaves; ++w) mm = fmaxf(mm, red_m[w][tid]);
+    for (int w = 0; w < kWaves; ++w) sum += red_l[w][tid] * exp2f(red_m[w][tid] - mm);
+    float* o = a.part + ((slice * a.n_chunks + chunk) * kMaxGroup + tid) * 2;
+    o[0] = mm;
+    o[1] = sum;
+  }
+}
+
+// Step kernel 2: normalisers, pooled group-mean weights added to the indicator of the cur + 1
+// scored rows, and this chunk's candidate for eviction: the smallest updated indicator, the later
+// row among equals.
+__global__ __launch_bounds__(kThreads) void step_apply_kernel(StepArgs a) {
+  __shared__ float lse_lds[kMaxGroup];
+  __shared__ float obs[kThreads + 2 * kMaxHalf];
+  __shared__ float cand_v[kWaves];
+  __shared__ int cand_j[kWaves];
+  const int chunk = blockIdx.x, ll = blockIdx.z;
+  const int b = blockIdx.y / a.h_kv, g = blockIdx.y % a.h_kv;
+  const int64_t slice = ((int64_t)ll * a.batch + b) * a.h_kv + g;
+  const int32_t* st = a.state[ll] + ((int64_t)b * a.h_kv + g) * 4;
+  const int cur1 = st[0] + 1;                              // scored rows, the newcomer included
+  const int n = cur1 + a.window;
+  if (chunk * kThreads >= cur1) return;
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  if (tid < a.group) {
+    const int used = (n + kThreads - 1) / kThreads;
+    const float* p = a.part + (slice * a.n_chunks * kMaxGroup + tid) * 2;
+    float mm = kMasked;
+    for (int c = 0; c < used; ++c) mm = fmaxf(mm, p[(int64_t)c * kMaxGroup * 2]);
+    float sum = 0.f;
+    for (int c = 0; c < used; ++c) sum += p[(int64_t)c * kMaxGroup * 2 + 1] * exp2f(p[(int64_t)c * kMaxGroup * 2] - mm);
+    lse_lds[tid] = mm + log2f(sum);
+  }
+  __syncthreads();
+  const int half = a.pool / 2;
+  const int j0 = chunk * kThreads - half;
+  const float* lg = a.logits + slice * a.rows_max * kMaxGroup;
+  for (int i = tid; i < kThreads + 2 * half; i += kThreads) {
+    const int j = j0 + i;
+    float w = -INFINITY;                                   // clipped edges never win the max
+    if (j >= 0 && j < cur1) {
+      float s = 0.f;
+#pragma unroll
+      for (int h = 0; h < kMaxGroup; ++h)
+        if (h < a.group) s += exp2f(lg[(int64_t)j * kMaxGroup + h] - lse_lds[h]);
+      w = s * a.inv_g;
+    }
+    obs[i] = w;
+  }
+  __syncthreads();
+  const int j = chunk * kThreads + tid;
+  float val = INFINITY;
+  int best = -1;
+  if (j < cur1) {
+    float mx = obs[tid + half];
+    for (int d = 1; d <= half; ++d) mx = fmaxf(mx, fmaxf(obs[tid + half - d], obs[tid + half + d]));
+    float* ind = a.indicator[ll] + ((int64_t)b * a.h_kv + g) * (a.cap[ll] + 1);
+    val = ind[j] + mx;
+    ind[j] = val;
+    best = j;
+  }
+#pragma unroll
+  for (int off = 32; off >= 1; off >>= 1) {
+    const float ov = __shfl_xor(val, off);
+    const int oj = __shfl_xor(best, off);
+    if (ov < val || (ov == val && oj > best)) { val = ov; best = oj; }
+  }
+  if (lane == 0) { cand_v[wave] = val; cand_j[wave] = best; }
+  __syncthreads();
+  if (tid == 0) {
+    for (int w = 1; w < kWaves; ++w)
+      if (cand_v[w] < val || (cand_v[w] == val && cand_j[w] > best)) { val = cand_v[w]; best = cand_j[w]; }
+    float* o = a.amin + (slice * a.n_chunks + chunk) * 2;
+    o[0] = val;
+    o[1] = __int_as_float(best);
+  }
+}
+
+// Step kernel 3: the row to evict over all chunks; it is deleted from the list and from the
+// indicator (the later entries move down by one), its slot becomes the free one.
+__global__ __launch_bounds__(kThreads) void step_evict_kernel(StepArgs a) {
+  __shared__ int evict_lds;
+  const int ll = blockIdx.y;
+  const int b = blockIdx.x / a.h_kv, g = blockIdx.x % a.h_kv;
+  const int64_t slice = ((int64_t)ll * a.batch + b) * a.h_kv + g;
+  int32_t* st = a.state[ll] + ((int64_t)b * a.h_kv + g) * 4;
+  const int cur = st[0], cur1 = cur + 1, n = cur1 + a.window;
+  const int cap = a.cap[ll];
+  const int tid = threadIdx.x;
+  int32_t* order = a.order[ll] + ((int64_t)b * a.h_kv + g) * (cap + a.window + 1);
+  float* ind = a.indicator[ll] + ((int64_t)b * a.h_kv + g) * (cap + 1);
+  if (tid == 0) {
+    const int used = (cur1 + kThreads - 1) / kThreads;
+    const float* p = a.amin + slice * a.n_chunks * 2;
+    float val = p[0];
+    int best = __float_as_int(p[1]);
+    for (int c = 1; c < used; ++c) {
+      const float v = p[2 * c];
+      const int jj = __float_as_int(p[2 * c + 1]);
+      if (v < val || (v == val && jj > best)) { val = v; best = jj; }
+    }
+    evict_lds = best;
+  }
+  __syncthreads();
+  const int e = evict_lds;
+  const int freed = order[e];
+  __syncthreads();
+  for (int base = e; base < n - 1; base += kThreads) {     // entries base+1.. move to base..: read all, then write
+    const int jj = base + tid;
+    const bool live = jj < n - 1;
+    const int32_t o = live ? order[jj + 1] : 0;
+    const float x = (live && jj + 1 < cur1) ? ind[jj + 1] : 0.f;
+    __syncthreads();
+    if (live) order[jj] = o;
+    if (live && jj + 1 < cur1) ind[jj] = x;
+    __syncthreads();
+  }
+  if (tid == 0) {
+    st[1] = freed;
+    st[2] = e;          // logical index of the evicted scored row (for inspection)
+  }
+}
+
 }  // namespace
 }  // namespace cake
 
@@ -330,4 +540,78 @@ extern "C" int cake_decode_update_static(const cake_shape* shape, const cake_par
   if (int rc = static_scratch(&ptr)) return rc;
   return decode_update_impl(shape, params, q_new, q_strides, k_cache, k_strides, cur_len, indicator,
                             static_cast<float*>(ptr), stream);
+}
+
+extern "C" int cake_decode_step_workspace_bytes(const cake_shape* shape, size_t* bytes) {
+  CAKE_REQUIRE(bytes != nullptr, "bytes is NULL");
+  if (int rc = check_shape_scores(shape)) return rc;
+  const size_t slices = (size_t)shape->n_layers * shape->batch * shape->n_kv_heads;
+  const size_t n_chunks = ((size_t)shape->seq_len + kThreads - 1) / kThreads;
+  *bytes = align_up(sizeof(float) * slices * shape->seq_len * kMaxGroup, 256) +
+           align_up(sizeof(float) * slices * n_chunks * kMaxGroup * 2, 256) + align_up(sizeof(float) * slices * n_chunks * 2, 256);
+  return CAKE_OK;
+}
+
+extern "C" int cake_decode_step(const cake_shape* shape, const cake_params* params,
+                                const void* q_new, const int64_t* q_strides,
+                                const void* k_new, const void* v_new, const int64_t* kv_new_strides,
+                                void* const* k_slots, void* const* v_slots, const int64_t* slot_strides,
+                                float* const* indicator, int32_t* const* order, int32_t* const* state,
+                                const int32_t* cap, void* workspace, size_t workspace_bytes, void* stream) {
+  if (int rc = check_shape_scores(shape)) return rc;
+  CAKE_REQUIRE(params != nullptr, "params is NULL");
+  CAKE_REQUIRE(q_new && k_new && v_new && k_slots && v_slots && indicator && order && state && q_strides && kv_new_strides &&
+                   slot_strides && cap, "a pointer argument is NULL");
+  CAKE_REQUIRE(params->pool_kernel >= 1 && params->pool_kernel % 2 == 1 && params->pool_kernel <= 129,
+               "pool_kernel %d must be odd and within [1, 129]", params->pool_kernel);
+  CAKE_REQUIRE(std::isfinite(params->scale) && params->scale >= 0.f, "scale must be finite and >= 0");
+  const int B = shape->batch, L = shape->n_layers, G = shape->n_q_heads / shape->n_kv_heads;
+  CAKE_REQUIRE(L <= kMaxLaunchLayers, "at most %d layers per cake_decode_step call", kMaxLaunchLayers);
+  const size_t eb = elem_bytes(shape->dtype);
+  for (int i = 0; i < 3; ++i) {
+    CAKE_REQUIRE(q_strides[i] >= 0 && kv_new_strides[i] >= 0 && slot_strides[i] >= 0, "negative stride");
+    CAKE_REQUIRE((q_strides[i] * eb) % 16 == 0 && (kv_new_strides[i] * eb) % 16 == 0 && (slot_strides[i] * eb) % 16 == 0,
+                 "strides must be multiples of 16 bytes");
+  }
+  for (int l = 0; l < L; ++l)
+    CAKE_REQUIRE(cap[l] >= 0 && cap[l] + shape->window + 1 <= shape->seq_len,
+                 "cap[%d] = %d: cap + window + 1 must not exceed shape.seq_len = %d", l, cap[l], shape->seq_len);
+  size_t need = 0;
+  if (int rc = cake_decode_step_workspace_bytes(shape, &need)) return rc;
+  if (workspace == nullptr || (reinterpret_cast<uintptr_t>(workspace) & 255) != 0)
+    return fail(CAKE_ERR_WORKSPACE, "workspace is NULL or not 256-byte aligned");
+  if (workspace_bytes < need) return fail(CAKE_ERR_WORKSPACE, "workspace has %zu bytes, %zu needed", workspace_bytes, need);
+
+  StepArgs a{};
+  a.q_new = q_new; a.k_new = k_new; a.v_new = v_new;
+  a.k_slots = k_slots; a.v_slots = v_slots; a.indicator = indicator; a.order = order; a.state = state;
+  for (int i = 0; i < 3; ++i) { a.qs[i] = q_strides[i]; a.ns[i] = kv_new_strides[i]; a.ss[i] = slot_strides[i]; }
+  a.batch = B; a.h_kv = shape->n_kv_heads; a.group = G; a.window = shape->window; a.pool = params->pool_kernel;
+  a.rows_max = shape->seq_len;
+  a.n_chunks = (shape->seq_len + kThreads - 1) / kThreads;
+  const double scale = params->scale > 0.f ? (double)params->scale : 1.0 / std::sqrt((double)shape->head_dim);
+  a.c = (float)(scale * 1.4426950408889634);
+  a.inv_g = 1.0f / (float)G;
+  const size_t slices = (size_t)L * B * shape->n_kv_heads;
+  char* ws = static_cast<char*>(workspace);
+  a.logits = reinterpret_cast<float*>(ws);
+  ws += align_up(sizeof(float) * slices * shape->seq_len * kMaxGroup, 256);
+  a.part = reinterpret_cast<float*>(ws);
+  ws += align_up(sizeof(float) * slices * a.n_chunks * kMaxGroup * 2, 256);
+  a.amin = reinterpret_cast<float*>(ws);
+  int cap_max = 0;
+  for (int l = 0; l < L; ++l) { a.cap[l] = cap[l]; cap_max = std::max(cap_max, cap[l]); }
+  hipStream_t st = static_cast<hipStream_t>(stream);
+  const int used = (cap_max + shape->window + 1 + kThreads - 1) / kThreads;
+  const dim3 grid(used, B * shape->n_kv_heads, L), block(kThreads);
+  const bool bf = shape->dtype == CAKE_BF16;
+  if (bf && shape->head_dim == 128) hipLaunchKernelGGL((step_logits_kernel<__bf16, 128>), grid, block, 0, st, a);
+  else if (bf && shape->head_dim == 64) hipLaunchKernelGGL((step_logits_kernel<__bf16, 64>), grid, block, 0, st, a);
+  else if (!bf && shape->head_dim == 128) hipLaunchKernelGGL((step_logits_kernel<float, 128>), grid, block, 0, st, a);
+  else if (!bf && shape->head_dim == 64) hipLaunchKernelGGL((step_logits_kernel<float, 64>), grid, block, 0, st, a);
+  else return fail(CAKE_ERR_UNSUPPORTED, "no decode kernel for this shape");
+  hipLaunchKernelGGL(step_apply_kernel, grid, block, 0, st, a);
+  hipLaunchKernelGGL(step_evict_kernel, dim3(B * shape->n_kv_heads, L), block, 0, st, a);
+  CAKE_HIP_TRY(hipGetLastError());
+  return CAKE_OK;
 }

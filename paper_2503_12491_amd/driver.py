@@ -485,3 +485,59 @@ class DecodeCache:
         self.k[l], self.v[l], self.ind[l] = k_out, v_out, i_out[:, :, :cap]
         self.last_idx = idx
         self._keep_alive = (q_new, k_in, v_in, i_in)       # until the kernels have run
+
+
+class DecodeSlots:
+    """The evicted caches of a prompt during generation, kept in place (cake_decode_step): every
+    layer's K and V sit in fixed slots, a per-head list gives the logical order, and a generated
+    token costs one key/value row write per head plus the indicator update.  All buffers, pointer
+    tables and the workspace are made once here; `step` allocates nothing."""
+
+    def __init__(self, result: PassResult, n_q_heads: int, window: int, params=None):
+        self.params = params if params is not None else C.make_params()
+        self.S_w, self.H_q = int(window), int(n_q_heads)
+        keep = np.asarray(result.keep, dtype=np.int64)                       # [L, B]
+        self.L, self.B = keep.shape
+        k0 = result.k_out[0]
+        self.H_kv, self.d, self.dtype, dev = k0.shape[1], k0.shape[3], k0.dtype, k0.device
+        self.cap = [int(keep[l].max()) for l in range(self.L)]
+        self.k, self.v, self.ind, self.order, self.state = [], [], [], [], []
+        for l in range(self.L):
+            cap, rows = self.cap[l], self.cap[l] + self.S_w + 1
+            k = torch.zeros(self.B, self.H_kv, rows, self.d, dtype=self.dtype, device=dev)
+            v = torch.zeros_like(k)
+            ind = torch.zeros(self.B, self.H_kv, cap + 1, dtype=torch.float32, device=dev)
+            order = torch.arange(rows, dtype=torch.int32, device=dev).repeat(self.B, self.H_kv, 1).contiguous()
+            state = torch.zeros(self.B, self.H_kv, 4, dtype=torch.int32, device=dev)
+            for b in range(self.B):
+                n_b = int(keep[l, b])
+                k[b, :, : n_b + self.S_w] = result.k_out[l][b, :, : n_b + self.S_w]
+                v[b, :, : n_b + self.S_w] = result.v_out[l][b, :, : n_b + self.S_w]
+                ind[b, :, :n_b] = result.ind_out[l][b, :, :n_b]
+                state[b, :, 0] = n_b
+                state[b, :, 1] = n_b + self.S_w                               # first unused slot
+            self.k.append(k); self.v.append(v); self.ind.append(ind); self.order.append(order); self.state.append(state)
+        self.tbl = {name: C.ptr_table(getattr(self, name)) for name in ("k", "v", "ind", "order", "state")}
+        rows_max = max(self.cap) + self.S_w + 1
+        self.shape1 = C.make_shape(self.B, 1, self.H_q, self.H_kv, self.d, rows_max, self.S_w, self.dtype)
+        self.ws = torch.empty(C.cake_decode_step_workspace_bytes(self.shape1), dtype=torch.uint8, device=dev)
+        self.slot_strides = [_strides3(t) for t in self.k]
+
+    def step(self, layer: int, q_new: torch.Tensor, k_new: torch.Tensor, v_new: torch.Tensor) -> None:
+        """q_new [B, H_q, d]; k_new, v_new [B, H_kv, d]: the generated token's projections at `layer`."""
+        l = layer
+        assert q_new.stride(2) == 1 and k_new.stride(2) == 1 and v_new.stride() == k_new.stride()
+        C.cake_decode_step(self.shape1, self.params, q_new, [0, q_new.stride(0), q_new.stride(1)], k_new, v_new,
+                           [0, k_new.stride(0), k_new.stride(1)], self.tbl["k"][l:l + 1], self.tbl["v"][l:l + 1],
+                           self.slot_strides[l], self.tbl["ind"][l:l + 1], self.tbl["order"][l:l + 1],
+                           self.tbl["state"][l:l + 1], [self.cap[l]], self.ws)
+
+    def logical(self, layer: int, b: int):
+        """(K, V [H_kv, cur + S_w, d], indicator [H_kv, cur], evicted logical index [H_kv]) of one
+        sequence in logical order: the view the method describes.  Inspection only."""
+        st = self.state[layer][b].cpu().numpy()
+        cur = int(st[0, 0])
+        order = self.order[layer][b, :, : cur + self.S_w].long()
+        gather = order[:, :, None].expand(-1, -1, self.d)
+        return (torch.gather(self.k[layer][b], 1, gather), torch.gather(self.v[layer][b], 1, gather),
+                self.ind[layer][b, :, :cur], st[:, 2].copy())
