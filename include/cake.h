@@ -144,6 +144,43 @@ int cake_window_scores_lse(const cake_shape* shape, const cake_params* params,
                            void* workspace, size_t workspace_bytes, void* stream);
 
 /*
+ * The same scores when the keys of a layer are not resident at once (a prompt whose K is
+ * produced, or paged in, a range of positions at a time): the softmax of Sec. 2 over all N keys
+ * needs every key twice, once for the row normalisers and once for the statistics of Eq. 4-5
+ * and Eq. 11, so the caller hands the key axis over in segments, twice:
+ *
+ *   for each segment:  cake_window_scores_segment(pass 1)      partial (max, sum) pairs per row
+ *   cake_window_scores_finish(pass 1)                          row normalisers, final
+ *   for each segment:  cake_window_scores_segment(pass 2)      un-pooled indicator, H/V partials
+ *   cake_window_scores_finish(pass 2)                          pooling -> indicator
+ *   cake_layer_preference(...)                                 as after cake_window_scores
+ *
+ * A segment is the key range [key_begin, key_begin + key_count): key_begin a multiple of
+ * cake_scores_chunk_keys(shape), the end a multiple of it or N.  The segments of a pass may come
+ * in any order and must cover [0, N) in pass 1 and [0, N_p) in pass 2 exactly once (pass-2
+ * segments may extend into the window; those keys are skipped).  The window queries are small
+ * (S_w rows) and are passed whole with every segment.  Work is split over the key axis at the
+ * same chunk boundaries and every partial result is reduced in the same fixed order as in
+ * cake_window_scores, so the outputs are bit-identical to those of one resident call.
+ *
+ *   k_segment  table; k_segment[l] -> [B, H_kv, key_count, d]: row 0 is key key_begin;
+ *              strides k_strides as for k.  Only read during the call.
+ *   workspace  the same buffer through the whole sequence of calls and into
+ *              cake_layer_preference, nothing else written to it in between.
+ * cake_window_scores_finish takes no q/k; `indicator` is written by pass 2's finish only (pass 1
+ * ignores it, may be NULL).  Errors as elsewhere: CAKE_ERR_ARGUMENT for a misaligned segment.
+ */
+int cake_scores_chunk_keys(const cake_shape* shape, int32_t* chunk /* host, out */);
+int cake_window_scores_segment(const cake_shape* shape, const cake_params* params, int32_t pass,
+                               int32_t key_begin, int32_t key_count,
+                               const void* const* q_win, const void* const* k_segment,
+                               const int64_t* q_strides, const int64_t* k_strides,
+                               void* workspace, size_t workspace_bytes, void* stream);
+int cake_window_scores_finish(const cake_shape* shape, const cake_params* params, int32_t pass,
+                              float* const* indicator,
+                              void* workspace, size_t workspace_bytes, void* stream);
+
+/*
  * Layer preference (Sec. 4.1 Eq. 6): H_l and V_l are the means over the layer's query heads
  * of H_h and V_h, reduced in a fixed order from the partial sums cake_window_scores left in
  * `workspace`; P_l = H_l^(1/tau1) * V_l^(1/tau2).

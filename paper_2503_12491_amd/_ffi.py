@@ -29,6 +29,13 @@ _SIGNATURES = {
     "cake_window_scores_lse": (ctypes.c_int, [ctypes.POINTER(cake_shape), ctypes.POINTER(cake_params), _P, _P,
                                               ctypes.POINTER(ctypes.c_int64), ctypes.POINTER(ctypes.c_int64), _P, _P,
                                               _P, ctypes.c_size_t, _P]),
+    "cake_scores_chunk_keys": (ctypes.c_int, [ctypes.POINTER(cake_shape), ctypes.POINTER(ctypes.c_int32)]),
+    "cake_window_scores_segment": (ctypes.c_int, [ctypes.POINTER(cake_shape), ctypes.POINTER(cake_params), ctypes.c_int32,
+                                                  ctypes.c_int32, ctypes.c_int32, _P, _P,
+                                                  ctypes.POINTER(ctypes.c_int64), ctypes.POINTER(ctypes.c_int64),
+                                                  _P, ctypes.c_size_t, _P]),
+    "cake_window_scores_finish": (ctypes.c_int, [ctypes.POINTER(cake_shape), ctypes.POINTER(cake_params), ctypes.c_int32,
+                                                 _P, _P, ctypes.c_size_t, _P]),
     "cake_layer_preference": (ctypes.c_int, [ctypes.POINTER(cake_shape), ctypes.POINTER(cake_params), _P,
                                              ctypes.c_size_t, _P, _P, _P]),
     "cake_cascade_allocate": (ctypes.c_int, [ctypes.POINTER(ctypes.c_double), ctypes.c_int32, ctypes.c_int64,

@@ -90,6 +90,26 @@ def cake_window_scores_lse(shape, params, q_win, k, q_strides, k_strides, row_ls
                                          _stream(stream)))
 
 
+def cake_scores_chunk_keys(shape: cake_shape) -> int:
+    out = ctypes.c_int32(0)
+    _check(load().cake_scores_chunk_keys(ctypes.byref(shape), ctypes.byref(out)))
+    return out.value
+
+
+def cake_window_scores_segment(shape, params, which_pass, key_begin, key_count, q_win, k_segment, q_strides, k_strides,
+                               workspace, stream=None) -> None:
+    _check(load().cake_window_scores_segment(ctypes.byref(shape), ctypes.byref(params), which_pass, key_begin, key_count,
+                                             _ptr(q_win), _ptr(k_segment), _i64(q_strides), _i64(k_strides),
+                                             _ptr(workspace), workspace.numel() * workspace.element_size(),
+                                             _stream(stream)))
+
+
+def cake_window_scores_finish(shape, params, which_pass, indicator, workspace, stream=None) -> None:
+    _check(load().cake_window_scores_finish(ctypes.byref(shape), ctypes.byref(params), which_pass, _ptr(indicator),
+                                            _ptr(workspace), workspace.numel() * workspace.element_size(),
+                                            _stream(stream)))
+
+
 def cake_layer_preference(shape, params, workspace, pref, hv=None, stream=None) -> None:
     _check(load().cake_layer_preference(ctypes.byref(shape), ctypes.byref(params), _ptr(workspace),
                                         workspace.numel() * workspace.element_size(), _ptr(pref), _ptr(hv),

@@ -94,6 +94,8 @@ struct ScoreArgs {
   float* const* indicator;
   int64_t qs[3], ks[3];      // element strides: batch, head, token
   int32_t batch, h_kv, group, n, n_p, chunk, n_chunks, n_chunks_p, pool;
+  int32_t key_lo, key_hi;    // keys [key_lo, key_hi) are behind the k pointers (row 0 = key key_lo); the whole layer: 0, n
+  int32_t chunk0;            // chunk of the first workgroup of a launch
   float c;                   // scale * log2(e): logits are handled in the log2 domain
   float inv_sw, inv_swc, inv_g;
   float w_mean, w_var, w_prod;   // I_q = w_mean*Mean + w_var*Var + w_prod*Mean*Var (Eq. 11 and the ablation's variants)
@@ -240,7 +242,7 @@ __global__ __launch_bounds__(512) void scores_pass1(ScoreArgs a) {
   // double buffer: tile t+1 is in flight while tile t is consumed (deeper rings measured no faster)
   __shared__ __attribute__((aligned(1024))) char tiles[2 * TL::kBytes];
 
-  const int chunk_id = blockIdx.x, slice = blockIdx.y;
+  const int chunk_id = blockIdx.x + a.chunk0, slice = blockIdx.y;
   int l, b, g;
   slice_coords(a, slice, l, b, g);
   const int w = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);   // wave index, known uniform
@@ -248,14 +250,16 @@ __global__ __launch_bounds__(512) void scores_pass1(ScoreArgs a) {
   const int n_waves = blockDim.x >> 6;
   constexpr int s_w = MB * 32;
   const T* q = reinterpret_cast<const T*>(a.q_win[l]) + b * a.qs[0] + (int64_t)(g * a.group + w) * a.qs[1];
-  const char* kbase = reinterpret_cast<const char*>(reinterpret_cast<const T*>(a.k[l]) + b * a.ks[0] + (int64_t)g * a.ks[1]);
   const int64_t tok_bytes = a.ks[2] * (int64_t)sizeof(T);
+  // address of key 0 of the slice (keys below key_lo are not behind the pointer and never touched)
+  const char* kbase = reinterpret_cast<const char*>(reinterpret_cast<const T*>(a.k[l]) + b * a.ks[0] + (int64_t)g * a.ks[1]) -
+                      (int64_t)a.key_lo * tok_bytes;
 
   const int key0 = chunk_id * a.chunk;
-  const int key_end = min(key0 + a.chunk, a.n);
+  const int key_end = min(key0 + a.chunk, min(a.n, a.key_hi));
   const int n_tiles = (key_end - key0 + kTileKeys - 1) / kTileKeys;
   TileMover<T, D> mover;
-  mover.init(kbase, tok_bytes, a.n - 1, w, n_waves, lane);
+  mover.init(kbase, tok_bytes, min(a.n, a.key_hi) - 1, w, n_waves, lane);
   mover.issue(tiles, key0);
 
   typename F::type qf[MB][kSteps];
@@ -459,7 +463,7 @@ __global__ __launch_bounds__(512) void scores_pass2(ScoreArgs a) {
   // stage in which the other is written, and a barrier separates the stages
   __shared__ float iq_lds[2][8][kTileKeys];
 
-  const int chunk_id = blockIdx.x, slice = blockIdx.y;
+  const int chunk_id = blockIdx.x + a.chunk0, slice = blockIdx.y;
   int l, b, g;
   slice_coords(a, slice, l, b, g);
   const int w = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);   // wave index, known uniform
@@ -467,14 +471,16 @@ __global__ __launch_bounds__(512) void scores_pass2(ScoreArgs a) {
   const int n_waves = blockDim.x >> 6;
   constexpr int s_w = MB * 32;
   const T* q = reinterpret_cast<const T*>(a.q_win[l]) + b * a.qs[0] + (int64_t)(g * a.group + w) * a.qs[1];
-  const char* kbase = reinterpret_cast<const char*>(reinterpret_cast<const T*>(a.k[l]) + b * a.ks[0] + (int64_t)g * a.ks[1]);
   const int64_t tok_bytes = a.ks[2] * (int64_t)sizeof(T);
+  // address of key 0 of the slice (keys below key_lo are not behind the pointer and never touched)
+  const char* kbase = reinterpret_cast<const char*>(reinterpret_cast<const T*>(a.k[l]) + b * a.ks[0] + (int64_t)g * a.ks[1]) -
+                      (int64_t)a.key_lo * tok_bytes;
 
   const int key0 = chunk_id * a.chunk;
-  const int key_end = min(key0 + a.chunk, a.n_p);
+  const int key_end = min(key0 + a.chunk, min(a.n_p, a.key_hi));
   const int n_tiles = (key_end - key0 + kTileKeys - 1) / kTileKeys;
   TileMover<T, D> mover;
-  mover.init(kbase, tok_bytes, a.n - 1, w, n_waves, lane);
+  mover.init(kbase, tok_bytes, min(a.n, a.key_hi) - 1, w, n_waves, lane);
   mover.issue(tiles, key0);
 
   typename F::type qf[MB][kSteps];
@@ -655,11 +661,30 @@ inline void mark(int i, hipStream_t stream) {
   if (g_profile.enabled && g_profile.created) (void)hipEventRecord(g_profile.ev[g_profile.calls % kProfileSets][i], stream);
 }
 
+// Which parts of the score stage a call runs: everything on a resident layer, or one of the
+// four steps of the segment-wise form (keys handed over a range at a time).
+enum ScoreParts { kPartsAll, kPartsPass1Segment, kPartsCombine, kPartsPass2Segment, kPartsPool };
+
 template <typename T, int D, int MB, bool kPivot>
-int launch_scores(const ScoreArgs& a, int64_t n_slices, const float* const* row_lse, hipStream_t stream) {
+int launch_scores(const ScoreArgs& a, int64_t n_slices, const float* const* row_lse, ScoreParts parts, hipStream_t stream) {
   dim3 block(64 * a.group);
   const int rows = a.group * MB * 32;
   const int64_t total_rows = n_slices * rows;
+  if (parts != kPartsAll) {
+    // chunks of this launch: those that hold keys of [key_lo, key_hi) (pass 2: below n_p as well)
+    const int hi1 = min(a.n, a.key_hi), hi2 = min(a.n_p, a.key_hi);
+    const int c1 = (hi1 - a.key_lo + a.chunk - 1) / a.chunk, c2 = hi2 > a.key_lo ? (hi2 - a.key_lo + a.chunk - 1) / a.chunk : 0;
+    if (parts == kPartsPass1Segment)
+      hipLaunchKernelGGL((scores_pass1<T, D, MB>), dim3(c1, (unsigned)n_slices), block, 0, stream, a);
+    else if (parts == kPartsCombine)
+      hipLaunchKernelGGL(scores_combine, dim3((unsigned)((total_rows * 4 + 255) / 256)), dim3(256), 0, stream, a, rows, total_rows);
+    else if (parts == kPartsPass2Segment && c2 > 0)
+      hipLaunchKernelGGL((scores_pass2<T, D, MB, kPivot>), dim3(c2, (unsigned)n_slices), block, 0, stream, a);
+    else if (parts == kPartsPool)
+      hipLaunchKernelGGL(pool_indicator, dim3((a.n_p + kPoolSpan - 1) / kPoolSpan, (unsigned)n_slices), dim3(256), 0, stream, a);
+    CAKE_HIP_TRY(hipGetLastError());
+    return CAKE_OK;
+  }
   mark(0, stream);
   if (row_lse == nullptr) {
     hipLaunchKernelGGL((scores_pass1<T, D, MB>), dim3(a.n_chunks, (unsigned)n_slices), block, 0, stream, a);
@@ -725,7 +750,8 @@ int window_scores_impl(const cake_shape* shape, const cake_params* params,
                        const void* const* q_win, const void* const* k,
                        const int64_t* q_strides, const int64_t* k_strides,
                        const float* const* row_lse, float* const* indicator,
-                       void* workspace, size_t workspace_bytes, void* stream) {
+                       void* workspace, size_t workspace_bytes, void* stream,
+                       ScoreParts parts = kPartsAll, int key_begin = 0, int key_count = 0) {
   if (int rc = check_shape_scores(shape)) return rc;
   CAKE_REQUIRE(params != nullptr, "params is NULL");
   CAKE_REQUIRE(q_win && k && indicator, "q_win, k or indicator table is NULL");
@@ -756,6 +782,15 @@ int window_scores_impl(const cake_shape* shape, const cake_params* params,
   a.batch = shape->batch; a.h_kv = shape->n_kv_heads; a.group = shape->n_q_heads / shape->n_kv_heads;
   a.n = shape->seq_len; a.n_p = shape->seq_len - shape->window;
   a.chunk = lay.chunk; a.n_chunks = lay.n_chunks; a.n_chunks_p = lay.n_chunks_p; a.pool = params->pool_kernel;
+  a.key_lo = 0; a.key_hi = a.n; a.chunk0 = 0;
+  if (parts == kPartsPass1Segment || parts == kPartsPass2Segment) {
+    CAKE_REQUIRE(key_begin >= 0 && key_count > 0 && (int64_t)key_begin + key_count <= a.n,
+                 "segment [%d, %d + %d) outside [0, seq_len = %d)", key_begin, key_begin, key_count, a.n);
+    CAKE_REQUIRE(key_begin % a.chunk == 0, "key_begin %d is not a multiple of the chunk of %d keys", key_begin, a.chunk);
+    CAKE_REQUIRE((key_begin + key_count) % a.chunk == 0 || key_begin + key_count == a.n,
+                 "a segment must end on a multiple of the chunk of %d keys or at seq_len", a.chunk);
+    a.key_lo = key_begin; a.key_hi = key_begin + key_count; a.chunk0 = key_begin / a.chunk;
+  }
   const int mode = params->indicator_mode;     // Eq. 11, or Mean, Var, Mean*Var of the indicator ablation
   a.w_mean = (mode == CAKE_IND_MEAN_PLUS_VAR || mode == CAKE_IND_MEAN) ? 1.f : 0.f;
   a.w_var = mode == CAKE_IND_MEAN_PLUS_VAR ? params->gamma : mode == CAKE_IND_VAR ? 1.f : 0.f;
@@ -776,8 +811,8 @@ int window_scores_impl(const cake_shape* shape, const cake_params* params,
   // pivoted column sums.  Eq. 11's sum and the plain mean do not need them.
   const bool pivot = mode == CAKE_IND_VAR || mode == CAKE_IND_MEAN_TIMES_VAR;
 #define CAKE_DISPATCH(T, D, MB)                                                         \
-  return pivot ? launch_scores<T, D, MB, true>(a, lay.n_slices, row_lse, st)            \
-               : launch_scores<T, D, MB, false>(a, lay.n_slices, row_lse, st)
+  return pivot ? launch_scores<T, D, MB, true>(a, lay.n_slices, row_lse, parts, st)     \
+               : launch_scores<T, D, MB, false>(a, lay.n_slices, row_lse, parts, st)
   const bool bf = shape->dtype == CAKE_BF16;
   const int d = shape->head_dim, mb = shape->window / 32;
   if (bf && d == 128 && mb == 1) CAKE_DISPATCH(__bf16, 128, 1);
@@ -810,6 +845,35 @@ extern "C" int cake_window_scores_lse(const cake_shape* shape, const cake_params
   CAKE_REQUIRE(row_lse != nullptr, "row_lse table is NULL");
   return window_scores_impl(shape, params, q_win, k, q_strides, k_strides, row_lse, indicator, workspace,
                             workspace_bytes, stream);
+}
+
+extern "C" int cake_scores_chunk_keys(const cake_shape* shape, int32_t* chunk) {
+  CAKE_REQUIRE(chunk != nullptr, "chunk is NULL");
+  if (int rc = check_shape_scores(shape)) return rc;
+  *chunk = score_layout(*shape).chunk;
+  return CAKE_OK;
+}
+
+extern "C" int cake_window_scores_segment(const cake_shape* shape, const cake_params* params, int32_t pass,
+                                          int32_t key_begin, int32_t key_count,
+                                          const void* const* q_win, const void* const* k_segment,
+                                          const int64_t* q_strides, const int64_t* k_strides,
+                                          void* workspace, size_t workspace_bytes, void* stream) {
+  CAKE_REQUIRE(pass == 1 || pass == 2, "pass %d must be 1 or 2", pass);
+  float* const* no_indicator = reinterpret_cast<float* const*>(workspace);    // not dereferenced by the segment kernels
+  return window_scores_impl(shape, params, q_win, k_segment, q_strides, k_strides, nullptr, no_indicator, workspace,
+                            workspace_bytes, stream, pass == 1 ? kPartsPass1Segment : kPartsPass2Segment, key_begin, key_count);
+}
+
+extern "C" int cake_window_scores_finish(const cake_shape* shape, const cake_params* params, int32_t pass,
+                                         float* const* indicator, void* workspace, size_t workspace_bytes, void* stream) {
+  CAKE_REQUIRE(pass == 1 || pass == 2, "pass %d must be 1 or 2", pass);
+  CAKE_REQUIRE(pass == 1 || indicator != nullptr, "indicator table is NULL");
+  static const int64_t unit[3] = {256, 256, 256};     // placeholders: these two kernels read neither q nor k
+  const void* const* none = reinterpret_cast<const void* const*>(workspace);
+  float* const* ind = pass == 2 ? indicator : reinterpret_cast<float* const*>(workspace);
+  return window_scores_impl(shape, params, none, none, unit, unit, nullptr, ind, workspace, workspace_bytes, stream,
+                            pass == 1 ? kPartsCombine : kPartsPool);
 }
 
 extern "C" int cake_layer_preference(const cake_shape* shape, const cake_params* params,

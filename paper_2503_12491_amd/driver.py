@@ -105,6 +105,32 @@ class EvictionPass:
                                      _strides3(self.k[0]), self.tbl_lse, self.tbl_ind, self.workspace, stream)
         C.cake_layer_preference(self.shape, self.params, self.workspace, self.pref, self.hv, stream)
 
+    def scores_segmented(self, segment_keys: int, fetch=None, stream=None) -> None:
+        """The score stage with the keys handed over `segment_keys` positions at a time (a
+        multiple of cake_scores_chunk_keys), as a caller would whose K is not resident: both
+        passes walk the segments, every segment copied into a staging buffer of that size first.
+        `fetch(l, lo, hi)` returns layer l's keys [B, H_kv, hi - lo, d]; the default slices self.k.
+        Bit-identical to scores()."""
+        chunk = C.cake_scores_chunk_keys(self.shape)
+        assert segment_keys > 0 and segment_keys % chunk == 0, f"segment of {segment_keys} keys is not a multiple of {chunk}"
+        fetch = fetch or (lambda l, lo, hi: self.k[l][:, :, lo:hi])
+        stage = [torch.empty(self.B, self.H_kv, min(segment_keys, self.N), self.d, dtype=self.dtype, device=self.dev)
+                 for _ in range(self.L)]
+        tbl = C.ptr_table(stage)
+        qs, ks = _strides3(self.q_win[0]), _strides3(stage[0])
+        for which, end in ((1, self.N), (2, self.N_p)):
+            for lo in range(0, end, segment_keys):
+                hi = min(lo + segment_keys, self.N)
+                for l in range(self.L):
+                    stage[l][:, :, : hi - lo].copy_(fetch(l, lo, hi))
+                    if hi - lo < stage[l].shape[2]:
+                        stage[l][:, :, hi - lo:].fill_(float("nan"))      # must never be read
+                C.cake_window_scores_segment(self.shape, self.params, which, lo, hi - lo, self.tbl_q, tbl, qs, ks,
+                                             self.workspace, stream)
+            C.cake_window_scores_finish(self.shape, self.params, which, self.tbl_ind if which == 2 else None,
+                                        self.workspace, stream)
+        C.cake_layer_preference(self.shape, self.params, self.workspace, self.pref, self.hv, stream)
+
     def preferences_to_host(self):
         """The pass's one device-to-host crossing: L*B preferences (and H, V)."""
         self.pref_host.copy_(self.pref, non_blocking=True)
