@@ -75,7 +75,12 @@ typedef enum {
   CAKE_IND_MEAN_PLUS_VAR = 0,  /* Mean + gamma*Var */
   CAKE_IND_MEAN = 1,           /* Mean (the SnapKV-style window mean) */
   CAKE_IND_VAR = 2,            /* Var */
-  CAKE_IND_MEAN_TIMES_VAR = 3  /* Mean * Var */
+  CAKE_IND_MEAN_TIMES_VAR = 3, /* Mean * Var */
+  CAKE_IND_CUMULATIVE = 4      /* sum over the S_w window rows = S_w * Mean: the accumulated-attention
+                                  (H2O-style) indicator of Sec. 5.5 under this allocation, taken over the
+                                  observation window.  Selects the same tokens as CAKE_IND_MEAN; the
+                                  stored values differ by the factor S_w, which matters once decode
+                                  steps add single attention rows to them. */
 } cake_indicator;
 
 /* Method parameters (Sec. 4.1 Eq. 6, Sec. 4.3 Eq. 11 and the implementation appendix). */
@@ -262,8 +267,9 @@ int cake_compact_kv(const cake_shape* shape,
  * layer's outputs, one layer after the other, in four caller-owned pools.  All of it is left in
  * `plan`, device memory of cake_plan_bytes(shape) bytes laid out as
  *   int32 budgets[L*B], keep[L*B], cur_len[L*B] (entry l*B + b), cap_keep[L], cap_cur[L]
- *   (cap = maximum over the batch), then from the next multiple of 8 bytes four tables of L
- *   device pointers: idx, k_out, v_out, ind_out;
+ *   (cap = maximum over the batch), copy_blocks[L*B + 1] (the compaction's work list: running
+ *   count of 1024-piece blocks of output rows), then from the next multiple of 8 bytes four
+ *   tables of L device pointers: idx, k_out, v_out, ind_out;
  * the host may copy it back at any later time to learn the budgets.
  * cake_evict_planned then runs cake_select_topk and cake_compact_kv for all layers with the
  * counts and output addresses taken from the plan (results identical to those two calls).

@@ -51,7 +51,8 @@ class OracleParams:
     tau2: float = 1.0
     var_correction: int = 1
     pool_kernel: int = 7
-    indicator_mode: int = 0         # 0 Mean + gamma*Var (Eq. 11); 1 Mean; 2 Var; 3 Mean*Var (indicator ablation)
+    indicator_mode: int = 0         # 0 Mean + gamma*Var (Eq. 11); 1 Mean; 2 Var; 3 Mean*Var (indicator ablation);
+                                    # 4 accumulated attention of the window rows (Sec. 5.5, H2O-style indicator)
 
 
 # ----------------------------------------------------------------------------------------
@@ -137,7 +138,9 @@ def layer_preference(h_heads: np.ndarray, v_heads: np.ndarray, tau1: float = 1.0
 # ----------------------------------------------------------------------------------------
 def head_indicator(a_obs: np.ndarray, gamma: float, var_correction: int = 1, mode: int = 0) -> np.ndarray:
     """Eq. (11), prefix case: Mean(A[-S_w:, n]) + gamma * Var(A[-S_w:, n]).  [H_q, N_p]
-    Modes 1-3 are the alternatives of the paper's indicator ablation: Mean, Var, Mean * Var."""
+    Modes 1-3 are the alternatives of the paper's indicator ablation: Mean, Var, Mean * Var.
+    Mode 4 is the accumulated-attention indicator of Sec. 5.5's compatibility experiment taken
+    over the observation window: the column sum of the S_w window rows."""
     s_w = a_obs.shape[-2]
     mean = np.sum(a_obs, axis=-2) / s_w
     var = column_variance(a_obs, var_correction)
@@ -149,6 +152,8 @@ def head_indicator(a_obs: np.ndarray, gamma: float, var_correction: int = 1, mod
         return var
     if mode == 3:
         return mean * var
+    if mode == 4:
+        return np.sum(a_obs, axis=-2)
     raise ValueError("indicator mode")
 
 

@@ -28,7 +28,7 @@ def make_shape(batch, n_layers, n_q_heads, n_kv_heads, head_dim, seq_len, window
     return cake_shape(batch, n_layers, n_q_heads, n_kv_heads, head_dim, seq_len, window, dtype)
 
 
-CAKE_IND_MEAN_PLUS_VAR, CAKE_IND_MEAN, CAKE_IND_VAR, CAKE_IND_MEAN_TIMES_VAR = 0, 1, 2, 3
+CAKE_IND_MEAN_PLUS_VAR, CAKE_IND_MEAN, CAKE_IND_VAR, CAKE_IND_MEAN_TIMES_VAR, CAKE_IND_CUMULATIVE = 0, 1, 2, 3, 4
 
 
 def make_params(scale=0.0, gamma=200.0, tau1=1.0, tau2=1.0, var_correction=1, pool_kernel=7,

@@ -64,10 +64,13 @@ struct LayerStrides {
 };
 
 // ---- device-resident eviction plan (cake_plan_eviction writes it, cake_evict_planned reads it) ----
-// int32 budgets[L*B], keep[L*B], cur_len[L*B], cap_keep[L], cap_cur[L]; then, 8-byte aligned,
-// four tables of L device pointers: idx, k_out, v_out, ind_out.
+// int32 budgets[L*B], keep[L*B], cur_len[L*B], cap_keep[L], cap_cur[L], copy_blocks[L*B + 1];
+// then, 8-byte aligned, four tables of L device pointers: idx, k_out, v_out, ind_out.
+// copy_blocks[e] = number of kCopyBlockPieces-piece blocks that the output rows of the entries
+// before e (entry l*B + b) fill, each entry rounded up: the planned compaction's work list.
+constexpr int kCopyBlockPieces = 1024;       // 16-byte pieces a compaction workgroup moves per step
 struct PlanLayout {
-  size_t off_budgets, off_keep, off_cur, off_cap_keep, off_cap_cur, off_tables, total;
+  size_t off_budgets, off_keep, off_cur, off_cap_keep, off_cap_cur, off_blocks, off_tables, total;
 };
 inline PlanLayout plan_layout(int n_layers, int batch) {
   PlanLayout p{};
@@ -78,6 +81,7 @@ inline PlanLayout plan_layout(int n_layers, int batch) {
   p.off_cur = off;      off += lb;
   p.off_cap_keep = off; off += l4;
   p.off_cap_cur = off;  off += l4;
+  p.off_blocks = off;   off += lb + sizeof(int32_t);
   off = align_up(off, 8);
   p.off_tables = off;   off += 4 * (size_t)n_layers * sizeof(void*);
   p.total = align_up(off, 256);
@@ -88,6 +92,7 @@ struct PlanView {               // device addresses inside a plan buffer
   const int32_t* cur_len;
   const int32_t* cap_keep;
   const int32_t* cap_cur;
+  const int32_t* copy_blocks;
   void* const* idx;
   void* const* k_out;
   void* const* v_out;
@@ -99,7 +104,7 @@ inline PlanView plan_view(const void* plan, int n_layers, int batch) {
   void* const* t = reinterpret_cast<void* const*>(b + lay.off_tables);
   return PlanView{reinterpret_cast<const int32_t*>(b + lay.off_keep), reinterpret_cast<const int32_t*>(b + lay.off_cur),
                   reinterpret_cast<const int32_t*>(b + lay.off_cap_keep), reinterpret_cast<const int32_t*>(b + lay.off_cap_cur),
-                  t, t + n_layers, t + 2 * n_layers, t + 3 * n_layers};
+                  reinterpret_cast<const int32_t*>(b + lay.off_blocks), t, t + n_layers, t + 2 * n_layers, t + 3 * n_layers};
 }
 // top-k and compaction of all layers with the counts and output places read from a plan
 int launch_topk_planned(const cake_shape* shape, const float* const* indicator, const PlanView& plan, hipStream_t stream);

@@ -33,16 +33,47 @@ struct CompactPlan {
   const int32_t* keep;        // [L*B]
   const int32_t* cap_cur;     // [L]
   const int32_t* cap_keep;    // [L]
+  const int32_t* copy_blocks; // [L*B + 1] running block counts (the work list)
+  int32_t n_entries;          // L*B
   int64_t s[3];
 };
+static_assert(kThreads * kUnroll == kCopyBlockPieces, "a workgroup step is one block of the plan's work list");
+constexpr int kListLds = 4096;       // work-list entries searched from LDS (longer lists are searched in memory)
 
-// A workgroup moves kThreads*kUnroll pieces at a time and strides over its (layer, sequence, head)
-// slice by the grid's x extent: launches that know the row counts cover a slice in one step,
-// planned launches (counts known only on the device) use a fixed extent.
+// A workgroup moves kThreads*kUnroll pieces of one (layer, sequence, head) slice per step.
+// Launches that know the row counts on the host give every slice the blocks it needs.  Planned
+// launches (counts known only on the device) run a fixed number of workgroups that stride over
+// the plan's work list, the blocks of all (layer, sequence) entries in one sequence, head by
+// blockIdx.y: the entry of a block is found by bisection of the running counts.
 template <bool kPlanned>
 __global__ __launch_bounds__(kThreads) void compact_kernel(CompactArgs a, RaggedDims dims, LayerStrides st, CompactPlan plan) {
-  const int ll = blockIdx.z;
-  const int b = blockIdx.y / a.h_kv, h = blockIdx.y % a.h_kv;
+  __shared__ int32_t list[kPlanned ? kListLds + 1 : 1];
+  const int32_t* blocks = plan.copy_blocks;
+  int32_t n_blocks = 1;
+  if (kPlanned) {
+    if (plan.n_entries <= kListLds) {
+      for (int i = threadIdx.x; i <= plan.n_entries; i += kThreads) list[i] = plan.copy_blocks[i];
+      __syncthreads();
+      blocks = list;
+    }
+    n_blocks = blocks[plan.n_entries];
+  }
+  const int32_t blk_end = kPlanned ? n_blocks : (int32_t)blockIdx.x + 1;      // host-sized launches: one step per workgroup
+  for (int32_t blk = blockIdx.x; blk < blk_end; blk += gridDim.x) {
+  int ll, b, h;
+  int64_t first;
+  if (kPlanned) {
+    int lo = 0, hi = plan.n_entries;          // largest e with blocks[e] <= blk (entries without blocks share a count)
+    while (hi - lo > 1) {
+      const int mid = (lo + hi) >> 1;
+      if (blocks[mid] <= blk) lo = mid; else hi = mid;
+    }
+    ll = lo / a.batch; b = lo % a.batch; h = blockIdx.y;
+    first = (int64_t)(blk - blocks[lo]) * (kThreads * kUnroll);
+  } else {
+    ll = blockIdx.z; b = blockIdx.y / a.h_kv; h = blockIdx.y % a.h_kv;
+    first = (int64_t)blockIdx.x * (kThreads * kUnroll);
+  }
   const int cur = kPlanned ? plan.cur_len[ll * a.batch + b] : dims.cur_len[ll * a.batch + b];
   const int keep = kPlanned ? plan.keep[ll * a.batch + b] : dims.keep[ll * a.batch + b];
   const int cap_cur = kPlanned ? plan.cap_cur[ll] : a.cap_cur[ll];
@@ -62,8 +93,7 @@ __global__ __launch_bounds__(kThreads) void compact_kernel(CompactArgs a, Ragged
   char* vout = static_cast<char*>(a.v_out[ll]) + out_off;
   const int32_t* idx = a.idx[ll] + ((int64_t)b * a.h_kv + h) * cap_keep;
 
-  for (int64_t first = (int64_t)blockIdx.x * (kThreads * kUnroll); first < total;
-       first += (int64_t)gridDim.x * (kThreads * kUnroll)) {
+  if (first >= total) { if (kPlanned) continue; else return; }
   uint4 kv[kUnroll], vv[kUnroll];
   int64_t dst[kUnroll];
 #pragma unroll
@@ -116,9 +146,11 @@ int cake::launch_compact_planned(const cake_shape* shape, const void* const* k_i
   a.batch = shape->batch; a.h_kv = shape->n_kv_heads; a.window = shape->window;
   a.pieces = shape->head_dim * eb / 16;
   a.elem_bytes = eb;
-  CompactPlan cp{plan.cur_len, plan.keep, plan.cap_cur, plan.cap_keep, {kv_strides[0], kv_strides[1], kv_strides[2]}};
-  // 64 workgroups stride over each (layer, sequence, head) slice: one step each up to 4096 rows of 16 pieces
-  hipLaunchKernelGGL(compact_kernel<true>, dim3(64, shape->batch * shape->n_kv_heads, shape->n_layers), dim3(kThreads), 0,
+  CompactPlan cp{plan.cur_len, plan.keep, plan.cap_cur, plan.cap_keep, plan.copy_blocks, shape->n_layers * shape->batch,
+                 {kv_strides[0], kv_strides[1], kv_strides[2]}};
+  // 8192 workgroups in all (a few rounds of what the chip holds at once), striding over the work list
+  const unsigned gx = (unsigned)std::max(1, 8192 / shape->n_kv_heads);
+  hipLaunchKernelGGL(compact_kernel<true>, dim3(gx, shape->n_kv_heads), dim3(kThreads), 0,
                      stream, a, RaggedDims{}, LayerStrides{}, cp);
   CAKE_HIP_TRY(hipGetLastError());
   return CAKE_OK;

@@ -171,11 +171,11 @@ __global__ __launch_bounds__(64) void allocate_kernel(const double* pref, int n_
   }
 }
 
-// Row capacities of every layer (the largest count over the batch) and the places of the
-// layers' outputs, one after the other, in the four pools.
+// Row capacities of every layer (the largest count over the batch), the places of the
+// layers' outputs, one after the other, in the four pools, and the compaction's work list.
 __global__ __launch_bounds__(64) void place_kernel(int n_layers, int batch, int h_kv, int window, int row_bytes,
                                                    const int32_t* keep, const int32_t* cur, int32_t* cap_keep,
-                                                   int32_t* cap_cur, char* pool_idx, char* pool_k, char* pool_v,
+                                                   int32_t* cap_cur, int32_t* copy_blocks, char* pool_idx, char* pool_k, char* pool_v,
                                                    char* pool_ind, void** idx_tbl, void** k_tbl, void** v_tbl,
                                                    void** ind_tbl) {
   const int lane = threadIdx.x;
@@ -190,17 +190,46 @@ __global__ __launch_bounds__(64) void place_kernel(int n_layers, int batch, int 
   }
   __threadfence_block();
   __syncthreads();
-  if (lane == 0) {
-    const int64_t bh = (int64_t)batch * h_kv;
-    int64_t off_i = 0, off_kv = 0;
-    for (int l = 0; l < n_layers; ++l) {
+  // Running sums over the layers (output places) and over the (layer, sequence) entries (the
+  // work list): every lane sums a run of consecutive items, a wave scan gives the runs' starts.
+  auto scan = [&](int64_t own) {           // exclusive prefix sum over the lanes
+    int64_t incl = own;
+#pragma unroll
+    for (int off = 1; off < 64; off <<= 1) {
+      const int64_t t = __shfl_up(incl, off);
+      if (lane >= off) incl += t;
+    }
+    return incl - own;
+  };
+  const int64_t bh = (int64_t)batch * h_kv;
+  {
+    const int per = (n_layers + 63) / 64;
+    const int l0 = min(lane * per, n_layers), l1 = min(l0 + per, n_layers);
+    int64_t rows = 0;
+    for (int l = l0; l < l1; ++l) rows += cap_keep[l];
+    int64_t before = scan(rows);            // rows of capacity in the layers before l0
+    for (int l = l0; l < l1; ++l) {
+      const int64_t off_i = bh * before, off_kv = bh * (before + (int64_t)l * window) * row_bytes;
       idx_tbl[l] = pool_idx + off_i * 4;
       ind_tbl[l] = pool_ind + off_i * 4;
       k_tbl[l] = pool_k + off_kv;
       v_tbl[l] = pool_v + off_kv;
-      off_i += bh * cap_keep[l];
-      off_kv += bh * (cap_keep[l] + window) * row_bytes;
+      before += cap_keep[l];
     }
+  }
+  {
+    const int64_t n = (int64_t)n_layers * batch, pieces = row_bytes / 16;
+    const int64_t per = (n + 63) / 64;
+    const int64_t e0 = min(lane * per, n), e1 = min(e0 + per, n);
+    auto blocks_of = [&](int64_t e) { return ((keep[e] + window) * pieces + kCopyBlockPieces - 1) / kCopyBlockPieces; };
+    int64_t own = 0;
+    for (int64_t e = e0; e < e1; ++e) own += blocks_of(e);
+    int64_t before = scan(own);
+    for (int64_t e = e0; e < e1; ++e) {
+      copy_blocks[e] = (int32_t)before;
+      before += blocks_of(e);
+    }
+    if (lane == 63) copy_blocks[n] = (int32_t)before;     // the last lane's run ends the list
   }
 }
 
@@ -237,13 +266,14 @@ extern "C" int cake_plan_eviction(const cake_shape* shape, const double* pref, i
   int32_t* cur = reinterpret_cast<int32_t*>(b + lay.off_cur);
   int32_t* cap_keep = reinterpret_cast<int32_t*>(b + lay.off_cap_keep);
   int32_t* cap_cur = reinterpret_cast<int32_t*>(b + lay.off_cap_cur);
+  int32_t* copy_blocks = reinterpret_cast<int32_t*>(b + lay.off_blocks);
   void** tables = reinterpret_cast<void**>(b + lay.off_tables);
   const int L = shape->n_layers;
   hipStream_t st = static_cast<hipStream_t>(stream);
   hipLaunchKernelGGL(allocate_kernel, dim3(shape->batch), dim3(64), 0, st, pref, L, shape->batch, total_budget,
                      shape->window, shape->seq_len, cur_len, budgets, keep, cur, status);
   hipLaunchKernelGGL(place_kernel, dim3(1), dim3(64), 0, st, L, shape->batch, shape->n_kv_heads, shape->window,
-                     (int)(shape->head_dim * elem_bytes(shape->dtype)), keep, cur, cap_keep, cap_cur,
+                     (int)(shape->head_dim * elem_bytes(shape->dtype)), keep, cur, cap_keep, cap_cur, copy_blocks,
                      static_cast<char*>(pool_idx), static_cast<char*>(pool_k), static_cast<char*>(pool_v),
                      static_cast<char*>(pool_ind), tables, tables + L, tables + 2 * L, tables + 3 * L);
   CAKE_HIP_TRY(hipGetLastError());

@@ -96,6 +96,7 @@ struct ScoreArgs {
   int32_t batch, h_kv, group, n, n_p, chunk, n_chunks, n_chunks_p, pool;
   int32_t key_lo, key_hi;    // keys [key_lo, key_hi) are behind the k pointers (row 0 = key key_lo); the whole layer: 0, n
   int32_t chunk0;            // chunk of the first workgroup of a launch
+  int32_t n_slices, pack;    // slices in all; slices that share a workgroup (packed kernels), else 1
   float c;                   // scale * log2(e): logits are handled in the log2 domain
   float inv_sw, inv_swc, inv_g;
   float w_mean, w_var, w_prod;   // I_q = w_mean*Mean + w_var*Var + w_prod*Mean*Var (Eq. 11 and the ablation's variants)
@@ -234,20 +235,52 @@ __device__ __forceinline__ void pass1_sums(const f32x16 (&acc)[MB], int kb, floa
   }
 }
 
-template <typename T, int D, int MB>
-__global__ __launch_bounds__(512) void scores_pass1(ScoreArgs a) {
+// Packed kernels (kPack): a.pack slices share a workgroup, G waves each, every slice with its own
+// tile buffers.  A workgroup's waves are dealt over the compute unit's four SIMDs in turn, so a
+// group of 5 or 6 heads alone leaves two waves on one SIMD and one on the others, and the
+// barriers make every wave wait for the doubled SIMD; three slices of 5 waves (or two of 6) fill
+// the SIMDs almost evenly.  Slices past the last one (the final workgroup) repeat the last
+// slice's work and store nothing.
+extern __shared__ __attribute__((aligned(1024))) char packed_lds[];
+
+struct WaveRole {
+  int slice, w;      // the wave's slice and its head within the group
+  int first_wave;    // index of the slice's first wave in the workgroup
+  bool live;         // false: a repeat of the last slice, stores nothing
+};
+template <bool kPack>
+__device__ __forceinline__ WaveRole wave_role(const ScoreArgs& a) {
+  const int w_all = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);   // wave index, known uniform
+  WaveRole r;
+  if (kPack) {
+    const int hg = w_all / a.group;
+    const int slice = blockIdx.y * a.pack + hg;
+    r.live = slice < a.n_slices;
+    r.slice = min(slice, a.n_slices - 1);
+    r.first_wave = hg * a.group;
+    r.w = w_all - r.first_wave;
+  } else {
+    r.slice = blockIdx.y; r.w = w_all; r.first_wave = 0; r.live = true;
+  }
+  return r;
+}
+
+template <typename T, int D, int MB, bool kPack>
+__global__ __launch_bounds__(kPack ? 1024 : 512) void scores_pass1(ScoreArgs a) {
   using F = Frag<T>;
   using TL = Tile<T, D>;
   constexpr int kSteps = D / F::kElems;
   // double buffer: tile t+1 is in flight while tile t is consumed (deeper rings measured no faster)
-  __shared__ __attribute__((aligned(1024))) char tiles[2 * TL::kBytes];
+  __shared__ __attribute__((aligned(1024))) char own_tiles[kPack ? 1024 : 2 * TL::kBytes];
 
-  const int chunk_id = blockIdx.x + a.chunk0, slice = blockIdx.y;
+  const WaveRole role = wave_role<kPack>(a);
+  const int chunk_id = blockIdx.x + a.chunk0, slice = role.slice;
   int l, b, g;
   slice_coords(a, slice, l, b, g);
-  const int w = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);   // wave index, known uniform
+  const int w = role.w;
+  char* tiles = kPack ? packed_lds + (role.first_wave / a.group) * (2 * TL::kBytes) : own_tiles;
   const int lane = threadIdx.x & 63, c32 = lane & 31, hh = lane >> 5;
-  const int n_waves = blockDim.x >> 6;
+  const int n_waves = a.group;
   constexpr int s_w = MB * 32;
   const T* q = reinterpret_cast<const T*>(a.q_win[l]) + b * a.qs[0] + (int64_t)(g * a.group + w) * a.qs[1];
   const int64_t tok_bytes = a.ks[2] * (int64_t)sizeof(T);
@@ -309,7 +342,7 @@ __global__ __launch_bounds__(512) void scores_pass1(ScoreArgs a) {
     float om = __shfl_xor(mref[nb], 32), ol = __shfl_xor(lsum[nb], 32);
     float m = fmaxf(mref[nb], om);
     float s = lsum[nb] * fast_exp2(mref[nb] - m) + ol * fast_exp2(om - m);
-    if (hh == 0) {
+    if (hh == 0 && role.live) {
       out[(nb * 32 + c32) * 2 + 0] = m;
       out[(nb * 32 + c32) * 2 + 1] = s;
     }
@@ -452,23 +485,31 @@ __device__ __forceinline__ void pass2_tile_stats(const ColSums& s0, const ColSum
   iq_row[lane] = fmaf(a.w_prod * mean, var, fmaf(a.w_var, var, a.w_mean * mean));
 }
 
-template <typename T, int D, int MB, bool kPivot>
-__global__ __launch_bounds__(512) void scores_pass2(ScoreArgs a) {
+constexpr int kPackMaxWaves = 16;      // waves of a packed workgroup
+
+template <typename T, int D, int MB, bool kPivot, bool kPack>
+__global__ __launch_bounds__(kPack ? 1024 : 512) void scores_pass2(ScoreArgs a) {
   using F = Frag<T>;
   using TL = Tile<T, D>;
   constexpr int kSteps = D / F::kElems;
   // double buffer: tile t+1 is in flight while tile t is consumed (deeper rings measured no faster)
-  __shared__ __attribute__((aligned(1024))) char tiles[2 * TL::kBytes];
+  __shared__ __attribute__((aligned(1024))) char own_tiles[kPack ? 1024 : 2 * TL::kBytes];
   // I_q of the G heads for two tiles in turn: the flush of one tile reads one buffer in the
   // stage in which the other is written, and a barrier separates the stages
-  __shared__ float iq_lds[2][8][kTileKeys];
+  __shared__ float own_iq[kPack ? 1 : 2 * 8 * kTileKeys];
 
-  const int chunk_id = blockIdx.x + a.chunk0, slice = blockIdx.y;
+  const WaveRole role = wave_role<kPack>(a);
+  const int chunk_id = blockIdx.x + a.chunk0, slice = role.slice;
   int l, b, g;
   slice_coords(a, slice, l, b, g);
-  const int w = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);   // wave index, known uniform
+  const int w = role.w;
+  char* tiles = kPack ? packed_lds + (role.first_wave / a.group) * (2 * TL::kBytes) : own_tiles;
+  constexpr int kIqWaves = kPack ? kPackMaxWaves : 8;
+  // [2][kIqWaves][64]; the packed kernels keep it behind the slices' tile buffers
+  float* iq_lds = kPack ? reinterpret_cast<float*>(packed_lds + a.pack * (2 * TL::kBytes)) : own_iq;
+  auto iq_row = [&](int buf, int wave) { return iq_lds + (buf * kIqWaves + role.first_wave + wave) * kTileKeys; };
   const int lane = threadIdx.x & 63, c32 = lane & 31, hh = lane >> 5;
-  const int n_waves = blockDim.x >> 6;
+  const int n_waves = a.group;
   constexpr int s_w = MB * 32;
   const T* q = reinterpret_cast<const T*>(a.q_win[l]) + b * a.qs[0] + (int64_t)(g * a.group + w) * a.qs[1];
   const int64_t tok_bytes = a.ks[2] * (int64_t)sizeof(T);
@@ -515,8 +556,8 @@ __global__ __launch_bounds__(512) void scores_pass2(ScoreArgs a) {
     if (t % n_waves != w) return;
     const int key = key0 + t * kTileKeys + lane;
     float s = 0.f;
-    for (int ww = 0; ww < a.group; ++ww) s += iq_lds[t & 1][ww][lane];
-    if (key < key_end) raw[key] = s * a.inv_g;
+    for (int ww = 0; ww < a.group; ++ww) s += iq_row(t & 1, ww)[lane];
+    if (key < key_end && role.live) raw[key] = s * a.inv_g;
   };
   // Tile t: its first sub-tile's MFMAs run beside the statistics of tile t-1's second sub-tile,
   // its second sub-tile's MFMAs beside the statistics of its first.  Only the last tile of a
@@ -541,7 +582,7 @@ __global__ __launch_bounds__(512) void scores_pass2(ScoreArgs a) {
       } else {
         // statistics of tile t-1's second sub-tile: never a tail, tile t-1 is not the last
         pass2_period<T, D, MB, true, true, false, kPivot>(cur, 0, qf, init, acc_a, acc_b, cv, true, entv, cs1, c32, hh);
-        pass2_tile_stats<kPivot>(cs0, cs1, a, hh, var_acc, &iq_lds[(t - 1) & 1][w][0], lane);
+        pass2_tile_stats<kPivot>(cs0, cs1, a, hh, var_acc, iq_row((t - 1) & 1, w), lane);
       }
       pass2_period<T, D, MB, true, true, kTail, kPivot>(cur, 1, qf, init, acc_b, acc_a, cv, v0, entv, cs0, c32, hh);
     } else {
@@ -549,7 +590,7 @@ __global__ __launch_bounds__(512) void scores_pass2(ScoreArgs a) {
       pass2_period<T, D, MB, false, true, kTail, kPivot>(cur, 0, qf, init, acc_a, acc_a, cv, v0, entv, cs0, c32, hh);
       pass2_period<T, D, MB, true, false, false, kPivot>(cur, 1, qf, init, acc_a, acc_a, cv, true, entv, cs1, c32, hh);
       pass2_period<T, D, MB, false, true, kTail, kPivot>(cur, 1, qf, init, acc_a, acc_a, cv, v1, entv, cs1, c32, hh);
-      pass2_tile_stats<kPivot>(cs0, cs1, a, hh, var_acc, &iq_lds[t & 1][w][0], lane);
+      pass2_tile_stats<kPivot>(cs0, cs1, a, hh, var_acc, iq_row(t & 1, w), lane);
     }
   };
   const bool last_partial = (key_end - key0) % kTileKeys != 0;
@@ -567,7 +608,7 @@ __global__ __launch_bounds__(512) void scores_pass2(ScoreArgs a) {
       pass2_period<T, D, MB, false, true, true, kPivot>(tiles, 0, qf, init, acc_a, acc_b, cv, v1, entv, cs1, c32, hh);
     else
       pass2_period<T, D, MB, false, true, false, kPivot>(tiles, 0, qf, init, acc_a, acc_b, cv, true, entv, cs1, c32, hh);
-    pass2_tile_stats<kPivot>(cs0, cs1, a, hh, var_acc, &iq_lds[(n_tiles - 1) & 1][w][0], lane);
+    pass2_tile_stats<kPivot>(cs0, cs1, a, hh, var_acc, iq_row((n_tiles - 1) & 1, w), lane);
   }
   __syncthreads();
   if (kFlushLag == 2 && n_tiles >= 2) flush(n_tiles - 2);
@@ -580,7 +621,7 @@ __global__ __launch_bounds__(512) void scores_pass2(ScoreArgs a) {
     ent_acc += __shfl_xor(ent_acc, off);
     var_acc += __shfl_xor(var_acc, off);
   }
-  if (lane == 0) {
+  if (lane == 0 && role.live) {
     float* o = a.hv + (((int64_t)slice * a.n_chunks_p + chunk_id) * a.group + w) * 2;
     o[0] = ent_acc;
     o[1] = var_acc;
@@ -665,9 +706,44 @@ inline void mark(int i, hipStream_t stream) {
 // four steps of the segment-wise form (keys handed over a range at a time).
 enum ScoreParts { kPartsAll, kPartsPass1Segment, kPartsCombine, kPartsPass2Segment, kPartsPool };
 
+// Slices per workgroup: group sizes whose waves would load the four SIMDs unevenly share a
+// workgroup (3 x 5 or 2 x 6 waves).  Only the kernels that fit 16 waves on a compute unit
+// (bf16, one row block) have a packed form.
+template <typename T, int MB>
+constexpr bool can_pack() { return sizeof(T) == 2 && MB == 1; }
+inline int slices_per_workgroup(int group) { return group == 5 ? 3 : group == 6 ? 2 : 1; }
+
 template <typename T, int D, int MB, bool kPivot>
 int launch_scores(const ScoreArgs& a, int64_t n_slices, const float* const* row_lse, ScoreParts parts, hipStream_t stream) {
-  dim3 block(64 * a.group);
+  dim3 block(64 * a.group * a.pack);
+  const unsigned gy = (unsigned)((n_slices + a.pack - 1) / a.pack);
+  const size_t packed_bytes = (size_t)a.pack * 2 * Tile<T, D>::kBytes + sizeof(float) * 2 * kPackMaxWaves * kTileKeys;
+  auto run_pass1 = [&](int chunks) -> hipError_t {
+    if constexpr (can_pack<T, MB>()) {
+      if (a.pack > 1) {
+        auto kern = scores_pass1<T, D, MB, true>;
+        if (hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
+                                               (int)packed_bytes); e != hipSuccess) return e;
+        hipLaunchKernelGGL(kern, dim3(chunks, gy), block, packed_bytes, stream, a);
+        return hipSuccess;
+      }
+    }
+    hipLaunchKernelGGL((scores_pass1<T, D, MB, false>), dim3(chunks, gy), block, 0, stream, a);
+    return hipSuccess;
+  };
+  auto run_pass2 = [&](int chunks) -> hipError_t {
+    if constexpr (can_pack<T, MB>()) {
+      if (a.pack > 1) {
+        auto kern = scores_pass2<T, D, MB, kPivot, true>;
+        if (hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
+                                               (int)packed_bytes); e != hipSuccess) return e;
+        hipLaunchKernelGGL(kern, dim3(chunks, gy), block, packed_bytes, stream, a);
+        return hipSuccess;
+      }
+    }
+    hipLaunchKernelGGL((scores_pass2<T, D, MB, kPivot, false>), dim3(chunks, gy), block, 0, stream, a);
+    return hipSuccess;
+  };
   const int rows = a.group * MB * 32;
   const int64_t total_rows = n_slices * rows;
   if (parts != kPartsAll) {
@@ -675,11 +751,11 @@ int launch_scores(const ScoreArgs& a, int64_t n_slices, const float* const* row_
     const int hi1 = min(a.n, a.key_hi), hi2 = min(a.n_p, a.key_hi);
     const int c1 = (hi1 - a.key_lo + a.chunk - 1) / a.chunk, c2 = hi2 > a.key_lo ? (hi2 - a.key_lo + a.chunk - 1) / a.chunk : 0;
     if (parts == kPartsPass1Segment)
-      hipLaunchKernelGGL((scores_pass1<T, D, MB>), dim3(c1, (unsigned)n_slices), block, 0, stream, a);
+      CAKE_HIP_TRY(run_pass1(c1));
     else if (parts == kPartsCombine)
       hipLaunchKernelGGL(scores_combine, dim3((unsigned)((total_rows * 4 + 255) / 256)), dim3(256), 0, stream, a, rows, total_rows);
     else if (parts == kPartsPass2Segment && c2 > 0)
-      hipLaunchKernelGGL((scores_pass2<T, D, MB, kPivot>), dim3(c2, (unsigned)n_slices), block, 0, stream, a);
+      CAKE_HIP_TRY(run_pass2(c2));
     else if (parts == kPartsPool)
       hipLaunchKernelGGL(pool_indicator, dim3((a.n_p + kPoolSpan - 1) / kPoolSpan, (unsigned)n_slices), dim3(256), 0, stream, a);
     CAKE_HIP_TRY(hipGetLastError());
@@ -687,7 +763,7 @@ int launch_scores(const ScoreArgs& a, int64_t n_slices, const float* const* row_
   }
   mark(0, stream);
   if (row_lse == nullptr) {
-    hipLaunchKernelGGL((scores_pass1<T, D, MB>), dim3(a.n_chunks, (unsigned)n_slices), block, 0, stream, a);
+    CAKE_HIP_TRY(run_pass1(a.n_chunks));
     mark(1, stream);
     hipLaunchKernelGGL(scores_combine, dim3((unsigned)((total_rows * 4 + 255) / 256)), dim3(256), 0, stream, a, rows, total_rows);
   } else {
@@ -697,7 +773,7 @@ int launch_scores(const ScoreArgs& a, int64_t n_slices, const float* const* row_
     mark(1, stream);
   }
   mark(2, stream);
-  hipLaunchKernelGGL((scores_pass2<T, D, MB, kPivot>), dim3(a.n_chunks_p, (unsigned)n_slices), block, 0, stream, a);
+  CAKE_HIP_TRY(run_pass2(a.n_chunks_p));
   mark(3, stream);
   hipLaunchKernelGGL(pool_indicator, dim3((a.n_p + kPoolSpan - 1) / kPoolSpan, (unsigned)n_slices), dim3(256), 0, stream, a);
   mark(4, stream);
@@ -758,7 +834,7 @@ int window_scores_impl(const cake_shape* shape, const cake_params* params,
   CAKE_REQUIRE(q_strides && k_strides, "q_strides or k_strides is NULL");
   CAKE_REQUIRE(params->pool_kernel >= 1 && params->pool_kernel % 2 == 1 && params->pool_kernel <= 2 * kPoolMaxHalf + 1,
                "pool_kernel %d must be odd and within [1, %d]", params->pool_kernel, 2 * kPoolMaxHalf + 1);
-  CAKE_REQUIRE(params->indicator_mode >= CAKE_IND_MEAN_PLUS_VAR && params->indicator_mode <= CAKE_IND_MEAN_TIMES_VAR,
+  CAKE_REQUIRE(params->indicator_mode >= CAKE_IND_MEAN_PLUS_VAR && params->indicator_mode <= CAKE_IND_CUMULATIVE,
                "indicator_mode %d is not a cake_indicator", params->indicator_mode);
   CAKE_REQUIRE(params->var_correction == 0 || params->var_correction == 1, "var_correction %d must be 0 or 1", params->var_correction);
   CAKE_REQUIRE(std::isfinite(params->gamma) && std::isfinite(params->scale) && params->scale >= 0.f, "gamma/scale must be finite, scale >= 0");
@@ -783,6 +859,8 @@ int window_scores_impl(const cake_shape* shape, const cake_params* params,
   a.n = shape->seq_len; a.n_p = shape->seq_len - shape->window;
   a.chunk = lay.chunk; a.n_chunks = lay.n_chunks; a.n_chunks_p = lay.n_chunks_p; a.pool = params->pool_kernel;
   a.key_lo = 0; a.key_hi = a.n; a.chunk0 = 0;
+  a.n_slices = (int32_t)lay.n_slices;
+  a.pack = (shape->dtype == CAKE_BF16 && shape->window == 32) ? slices_per_workgroup(a.group) : 1;
   if (parts == kPartsPass1Segment || parts == kPartsPass2Segment) {
     CAKE_REQUIRE(key_begin >= 0 && key_count > 0 && (int64_t)key_begin + key_count <= a.n,
                  "segment [%d, %d + %d) outside [0, seq_len = %d)", key_begin, key_begin, key_count, a.n);
@@ -791,8 +869,9 @@ int window_scores_impl(const cake_shape* shape, const cake_params* params,
                  "a segment must end on a multiple of the chunk of %d keys or at seq_len", a.chunk);
     a.key_lo = key_begin; a.key_hi = key_begin + key_count; a.chunk0 = key_begin / a.chunk;
   }
-  const int mode = params->indicator_mode;     // Eq. 11, or Mean, Var, Mean*Var of the indicator ablation
-  a.w_mean = (mode == CAKE_IND_MEAN_PLUS_VAR || mode == CAKE_IND_MEAN) ? 1.f : 0.f;
+  const int mode = params->indicator_mode;     // Eq. 11; Mean, Var, Mean*Var of the indicator ablation; the window's column sum
+  a.w_mean = (mode == CAKE_IND_MEAN_PLUS_VAR || mode == CAKE_IND_MEAN) ? 1.f
+             : mode == CAKE_IND_CUMULATIVE ? (float)shape->window : 0.f;     // Sec. 5.5: column sum = S_w * Mean
   a.w_var = mode == CAKE_IND_MEAN_PLUS_VAR ? params->gamma : mode == CAKE_IND_VAR ? 1.f : 0.f;
   a.w_prod = mode == CAKE_IND_MEAN_TIMES_VAR ? 1.f : 0.f;
   const double scale = params->scale > 0.f ? (double)params->scale : 1.0 / std::sqrt((double)shape->head_dim);

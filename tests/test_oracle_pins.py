@@ -87,7 +87,39 @@ def test_worked_example_indicator_ablation_modes(head):
     np.testing.assert_allclose(co.head_indicator(a_obs, 200.0, 1, mode=0)[0],
                                [float(m + 200 * v) for m, v in zip(mean, var)], rtol=1e-13)
     with pytest.raises(ValueError):
-        co.head_indicator(a_obs, 200.0, 1, mode=4)
+        co.head_indicator(a_obs, 200.0, 1, mode=5)
+
+
+def test_accumulated_attention_indicator_is_the_window_column_sum():
+    """Mode 4 (accumulated attention, Sec. 5.5) over the window: per head the sum of the worked
+    example's stored attention entries down each prefix column (exact rationals); S_w times the
+    mean-only indicator through the whole layer pass; hence the same selection as mode 1 at
+    every k, while a decode step (which adds one attention row) moves it S_w times less."""
+    g, q, k = _example_inputs(["head0", "head1"])
+    a_obs = co.observed(co.window_attention(q, k, scale=1.0), 2)
+    for i, head in enumerate(("head0", "head1")):
+        rows = [[Fraction(x) for x in row] for row in g[head]["a_obs"]]
+        want = [float(sum(col)) for col in zip(*rows)]
+        np.testing.assert_allclose(co.head_indicator(a_obs, 200.0, 1, mode=4)[i], want, rtol=1e-14)
+    rng = np.random.default_rng(11)
+    q = rng.standard_normal((4, 8, 16)) * 2
+    k = rng.standard_normal((2, 90, 16))
+    p1 = co.OracleParams(pool_kernel=5, indicator_mode=1)
+    p4 = co.OracleParams(pool_kernel=5, indicator_mode=4)
+    i1, i4 = co.layer_pass(q, k, p1)["indicator"], co.layer_pass(q, k, p4)["indicator"]
+    np.testing.assert_allclose(i4, 8 * i1, rtol=1e-14)
+    # brute force: softmax over the visible keys written out, summed down the window rows
+    n_p = 90 - 8
+    for h in range(4):
+        acc = np.zeros(n_p)
+        for r in range(8):
+            z = (q[h, r] @ k[h // 2, : n_p + r + 1].T) / 4.0
+            w = np.exp(z - z.max())
+            acc += (w / w.sum())[:n_p]
+        np.testing.assert_allclose(co.head_indicator(co.observed(co.window_attention(q, k), 8), 0.0, 1, mode=4)[h], acc, rtol=1e-12)
+    for kk in (0, 1, 7, 40, n_p):
+        for gi in range(2):
+            np.testing.assert_array_equal(co.select_topk(i4[gi], kk), co.select_topk(i1[gi], kk))
 
 
 def test_indicator_modes_through_layer_pass():

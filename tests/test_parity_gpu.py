@@ -352,9 +352,10 @@ def test_pass_batch_has_per_sequence_budgets(cake):
     assert res.budgets.shape == (3, 2)
 
 
-@pytest.mark.parametrize("mode", [1, 2, 3])
+@pytest.mark.parametrize("mode", [1, 2, 3, 4])
 def test_pass_indicator_ablation_modes(cake, mode):
-    # Mean, Var and Mean*Var in place of Mean + gamma*Var (the paper's indicator ablation)
+    # Mean, Var and Mean*Var in place of Mean + gamma*Var (the paper's indicator ablation), and the
+    # accumulated attention of the window rows (Sec. 5.5)
     say(f"pass indicator mode {mode}")
     cfg = CONFIGS[2].scaled(n_layers=2, seq_len=2048 + 32 + 19, total_budget=2 * 400)
     _check_pass(cake, cfg, cake.make_params(indicator_mode=mode))

@@ -32,7 +32,7 @@ def _case(rng):
     frac = rng.choice([0.1, 0.3, 0.8, 2.0])
     total = int(max(L * window + 1, L * (window + frac * n_p)))
     params = dict(gamma=float(rng.choice([0.0, 50.0, 200.0])), pool_kernel=int(rng.choice([1, 3, 7])),
-                  var_correction=int(rng.choice([0, 1])), indicator_mode=int(rng.choice([0, 0, 0, 1, 2, 3])),
+                  var_correction=int(rng.choice([0, 1])), indicator_mode=int(rng.choice([0, 0, 0, 1, 2, 3, 4])),
                   tau1=float(rng.choice([0.5, 1.0, 2.0])), tau2=float(rng.choice([0.5, 1.0, 3.0])))
     return group, h_kv, d, window, dtype, B, L, N, total, params
 
