@@ -36,7 +36,8 @@ def parse_args():
                     help="variant: hand the window rows' log-sum-exp to the library (cake_window_scores_lse), "
                          "as a prefill attention kernel would; the scores then read K once")
     ap.add_argument("--copy-calibration", action="store_true",
-                    help="also run a plain 1 GiB device copy four times (reference for the HBM byte counters)")
+                    help="also run a plain 1 GiB device copy and a sparse 256-byte-row gather four times each "
+                         "(references for the HBM byte counters)")
     ap.add_argument("--flush-cache", action="store_true",
                     help="overwrite a 1 GiB buffer before every step (outside the per-step event bracket), so that small "
                          "configs start every pass with cold L2 and last-level cache; adds ms_per_step_flushed")
@@ -156,7 +157,15 @@ def main():
         for _ in range(4):
             dst.copy_(src)
         torch.cuda.synchronize()
-        del src, dst
+        # and a sparse gather of 256-byte rows (every 16th row on average, ascending), the access
+        # pattern of the compaction: 2^18 rows of a 1 GiB table -> 64 MiB read, 64 MiB written
+        table = src.view(torch.bfloat16).view(-1, 128)
+        g = torch.Generator(device="cpu").manual_seed(1)
+        rows = torch.sort(torch.randperm(table.shape[0], generator=g)[: 1 << 18]).values.to(dev)
+        for _ in range(4):
+            picked = table.index_select(0, rows)
+        torch.cuda.synchronize()
+        del src, dst, table, rows, picked
 
     for _ in range(args.warmup):
         ev.run()

@@ -40,6 +40,12 @@ struct CompactPlan {
 static_assert(kThreads * kUnroll == kCopyBlockPieces, "a workgroup step is one block of the plan's work list");
 constexpr int kListLds = 4096;       // work-list entries searched from LDS (longer lists are searched in memory)
 
+typedef unsigned u32x4 __attribute__((ext_vector_type(4)));
+__device__ __forceinline__ void store_streaming(char* dst, const uint4& x) {
+  const u32x4 v = {x.x, x.y, x.z, x.w};
+  __builtin_nontemporal_store(v, reinterpret_cast<u32x4*>(dst));
+}
+
 // A workgroup moves kThreads*kUnroll pieces of one (layer, sequence, head) slice per step.
 // Launches that know the row counts on the host give every slice the blocks it needs.  Planned
 // launches (counts known only on the device) run a fixed number of workgroups that stride over
@@ -110,11 +116,13 @@ __global__ __launch_bounds__(kThreads) void compact_kernel(CompactArgs a, Ragged
       dst[u] = (int64_t)r * out_row + piece * 16;
     }
   }
+  // Streaming stores: the compacted rows are not read again by this pass, and plain stores were
+  // measured to cost twice their bytes in memory writes (the rows pass through the cache first).
 #pragma unroll
   for (int u = 0; u < kUnroll; ++u)
     if (dst[u] >= 0) {
-      *reinterpret_cast<uint4*>(kout + dst[u]) = kv[u];
-      *reinterpret_cast<uint4*>(vout + dst[u]) = vv[u];
+      store_streaming(kout + dst[u], kv[u]);
+      store_streaming(vout + dst[u], vv[u]);
     }
 
   // indicator entries of the retained prefix positions

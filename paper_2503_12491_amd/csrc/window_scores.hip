@@ -714,11 +714,21 @@ constexpr bool can_pack() { return sizeof(T) == 2 && MB == 1; }
 inline int slices_per_workgroup(int group) { return group == 5 ? 3 : group == 6 ? 2 : 1; }
 
 template <typename T, int D, int MB, bool kPivot>
-int launch_scores(const ScoreArgs& a, int64_t n_slices, const float* const* row_lse, ScoreParts parts, hipStream_t stream) {
-  dim3 block(64 * a.group * a.pack);
-  const unsigned gy = (unsigned)((n_slices + a.pack - 1) / a.pack);
-  const size_t packed_bytes = (size_t)a.pack * 2 * Tile<T, D>::kBytes + sizeof(float) * 2 * kPackMaxWaves * kTileKeys;
+int launch_scores(const ScoreArgs& a_in, int64_t n_slices, const float* const* row_lse, ScoreParts parts, hipStream_t stream) {
+  ScoreArgs a = a_in;
+  const bool packing = a_in.pack > 1;
+  auto set_pack = [&](int pass, dim3& block, unsigned& gy, size_t& packed_bytes) {
+    (void)pass;
+    a.pack = packing ? slices_per_workgroup(a.group) : 1;
+    block = dim3(64 * a.group * a.pack);
+    gy = (unsigned)((n_slices + a.pack - 1) / a.pack);
+    packed_bytes = (size_t)a.pack * 2 * Tile<T, D>::kBytes + sizeof(float) * 2 * kPackMaxWaves * kTileKeys;
+  };
+  dim3 block;
+  unsigned gy;
+  size_t packed_bytes;
   auto run_pass1 = [&](int chunks) -> hipError_t {
+    set_pack(1, block, gy, packed_bytes);
     if constexpr (can_pack<T, MB>()) {
       if (a.pack > 1) {
         auto kern = scores_pass1<T, D, MB, true>;
@@ -732,6 +742,7 @@ int launch_scores(const ScoreArgs& a, int64_t n_slices, const float* const* row_
     return hipSuccess;
   };
   auto run_pass2 = [&](int chunks) -> hipError_t {
+    set_pack(2, block, gy, packed_bytes);
     if constexpr (can_pack<T, MB>()) {
       if (a.pack > 1) {
         auto kern = scores_pass2<T, D, MB, kPivot, true>;
