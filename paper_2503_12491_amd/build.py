@@ -13,6 +13,9 @@ OBJ_DIR = os.path.join(ROOT, "_build")
 LIB_PATH = os.path.join(PKG, "libcake.so")
 
 SOURCES = ["cake_host.cpp", "window_scores.hip", "select_topk.hip", "compact_kv.hip", "decode_update.hip", "plan_evict.hip"]
+# standalone issue-rate microbenchmark (not part of the library): `python -m paper_2503_12491_amd.build --microbench`
+MICROBENCH_SRC = os.path.join(CSRC, "microbench", "issue_port.hip")
+MICROBENCH_PATH = os.path.join(PKG, "issue_port_microbench")
 
 COMMON = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC",
@@ -58,5 +61,17 @@ def build(verbose: bool = False) -> str:
     return LIB_PATH
 
 
+def build_microbench() -> str:
+    """Compile the issue-rate microbenchmark into paper_2503_12491_amd/issue_port_microbench."""
+    cmd = [_hipcc(), "--offload-arch=gfx950", "-O3", "-std=c++17", "-Xclang", "-target-feature", "-Xclang",
+           "-packed-fp32-ops", MICROBENCH_SRC, "-o", MICROBENCH_PATH]
+    res = subprocess.run(cmd, capture_output=True, text=True)
+    if res.returncode != 0:
+        raise RuntimeError(f"hipcc failed on the microbenchmark:\n{res.stderr}")
+    return MICROBENCH_PATH
+
+
 if __name__ == "__main__":
     print(build(verbose=True))
+    if "--microbench" in sys.argv[1:]:
+        print(build_microbench())

@@ -143,7 +143,7 @@ struct TileMover {
       for (int i = wave; i < TL::kGroups; i += n_waves) {
         const uint32_t group_bits = (uint32_t)(((i * kRows) & (TL::kPieces - 1)) << 4);
         const char* src = base + (int64_t)i * kRows * tok_bytes + (row_off + (piece_off ^ group_bits));
-        __builtin_amdgcn_global_load_lds((global_cptr)src, (lds_ptr)(tile + i * 1024), 16, 0, kStreamPolicy);
+        __builtin_amdgcn_global_load_lds((global_cptr)src, (lds_ptr)(tile + i * 1024), 16, 0, 0);
       }
     } else {
       for (int i = wave; i < TL::kGroups; i += n_waves) {
@@ -151,7 +151,7 @@ struct TileMover {
         const int r = off / TL::kRowBytes, slot = (off % TL::kRowBytes) >> 4;
         const int q = slot ^ (r & (TL::kPieces - 1));
         const char* src = kbase + (int64_t)min(t0 + r, last_key) * tok_bytes + q * 16;
-        __builtin_amdgcn_global_load_lds((global_cptr)src, (lds_ptr)(tile + i * 1024), 16, 0, kStreamPolicy);
+        __builtin_amdgcn_global_load_lds((global_cptr)src, (lds_ptr)(tile + i * 1024), 16, 0, 0);
       }
     }
   }
@@ -309,9 +309,10 @@ __global__ __launch_bounds__(kPack ? 1024 : 512) void scores_pass1(ScoreArgs a) 
   float cv = a.c;
   asm volatile("" : "+v"(cv));     // a vector register: a scalar operand halves the issue rate of the multiply
 
-  // The MFMAs of a 32-key sub-tile, then the exponentials and sums of its logits; with three
-  // waves per SIMD the phases of different waves overlap (an explicit software pipeline over two
-  // accumulator sets measured slower here).
+  // The MFMAs of a 32-key sub-tile, then the exponentials and sums of its logits.  An explicit
+  // software pipeline over two accumulator sets (each k-step's MFMAs followed by a share of the
+  // previous sub-tile's vector work, as in pass 2) measured 10 % slower here: it costs a wave
+  // per SIMD in registers, and under the chip's power limit overlapping the two pipes buys no time.
   f32x16 acc[MB];
   auto tail_of = [&](int kb) { return kb + 31 > a.n_p; };      // some key of the sub-tile may be hidden or past the end
 
