@@ -41,6 +41,9 @@ def parse_args():
     ap.add_argument("--flush-cache", action="store_true",
                     help="overwrite a 1 GiB buffer before every step (outside the per-step event bracket), so that small "
                          "configs start every pass with cold L2 and last-level cache; adds ms_per_step_flushed")
+    ap.add_argument("--decode", action="store_true",
+                    help="instead of the prefill pass: time the decode-phase cache maintenance of one generated token "
+                         "over all layers (in-place step, and the append + compaction form beside it)")
     ap.add_argument("--host-allocation", action="store_true",
                     help="variant: budgets on the host (cake_cascade_allocate) between the scores and EVICT")
     return ap.parse_args()
@@ -99,6 +102,43 @@ def measured_traffic(cfg, kernel):
         return None
 
 
+def decode_bench(cake, cfg, ev, steps, warmup):
+    """One generated token's cache maintenance in every layer (new query/key/value rows of synthetic
+    values), after one prefill pass of the config: microseconds per layer per token on the stream."""
+    import torch
+    res = ev.run()
+    torch.cuda.synchronize()
+    dev = ev.dev
+    g = torch.Generator().manual_seed(0)
+    qn = torch.randn(cfg.batch, cfg.n_q_heads, cfg.head_dim, generator=g).to(cfg.torch_dtype).to(dev)
+    kn = torch.randn(cfg.batch, cfg.n_kv_heads, cfg.head_dim, generator=g).to(cfg.torch_dtype).to(dev)
+    L = cfg.n_layers
+    out = {}
+    for name, cache in (("in_place_step", cake.DecodeSlots(res, cfg.n_q_heads, cfg.window)),
+                        ("append_and_compact", cake.DecodeCache(res, cfg.n_q_heads, cfg.window))):
+        for _ in range(warmup):
+            for l in range(L):
+                cache.step(l, qn, kn, kn)
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        t0 = time.perf_counter()
+        e0.record()
+        for _ in range(steps):
+            for l in range(L):
+                cache.step(l, qn, kn, kn)
+        e1.record()
+        torch.cuda.synchronize()
+        wall = (time.perf_counter() - t0) / steps
+        out[name] = {"us_per_layer_stream": e0.elapsed_time(e1) / steps / L * 1e3, "us_per_layer_wall": wall / L * 1e6,
+                     "ms_per_token_wall": wall * 1e3}
+    print(json.dumps({"metric": "decode cache maintenance per generated token", "unit": "us per layer", "n_gpus": 1,
+                      "value": out["in_place_step"]["us_per_layer_stream"], "higher_is_better": False, "steps": steps,
+                      "warmup": warmup, "dtype": cfg.dtype, "data": "synthetic",
+                      "config": {"workload": f"config {cfg.cid} ({cfg.name}) after one prefill pass: {L} layers, rows per head "
+                                             f"{int(res.keep.min())}..{int(res.keep.max())} + window {cfg.window}"},
+                      "variants": out}))
+
+
 def main():
     args = parse_args()
     if args.gpus != 1:
@@ -149,6 +189,10 @@ def main():
             del qf, s_, tail
     ev = cake.EvictionPass([q_all[l] for l in range(L)], [k_all[l] for l in range(L)], [v_all[l] for l in range(L)],
                            cfg.total_budget, params, row_lse=row_lse)
+
+    if args.decode:
+        decode_bench(cake, cfg, ev, args.steps, args.warmup)
+        return
 
     if args.copy_calibration:
         src = torch.empty(1 << 30, dtype=torch.uint8, device=dev).fill_(1)

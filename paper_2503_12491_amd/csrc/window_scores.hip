@@ -143,7 +143,7 @@ struct TileMover {
       for (int i = wave; i < TL::kGroups; i += n_waves) {
         const uint32_t group_bits = (uint32_t)(((i * kRows) & (TL::kPieces - 1)) << 4);
         const char* src = base + (int64_t)i * kRows * tok_bytes + (row_off + (piece_off ^ group_bits));
-        __builtin_amdgcn_global_load_lds((global_cptr)src, (lds_ptr)(tile + i * 1024), 16, 0, 0);
+        __builtin_amdgcn_global_load_lds((global_cptr)src, (lds_ptr)(tile + i * 1024), 16, 0, kStreamPolicy);
       }
     } else {
       for (int i = wave; i < TL::kGroups; i += n_waves) {
@@ -151,7 +151,7 @@ struct TileMover {
         const int r = off / TL::kRowBytes, slot = (off % TL::kRowBytes) >> 4;
         const int q = slot ^ (r & (TL::kPieces - 1));
         const char* src = kbase + (int64_t)min(t0 + r, last_key) * tok_bytes + q * 16;
-        __builtin_amdgcn_global_load_lds((global_cptr)src, (lds_ptr)(tile + i * 1024), 16, 0, 0);
+        __builtin_amdgcn_global_load_lds((global_cptr)src, (lds_ptr)(tile + i * 1024), 16, 0, kStreamPolicy);
       }
     }
   }
@@ -276,7 +276,8 @@ __global__ __launch_bounds__(kPack ? 1024 : 512) void scores_pass1(ScoreArgs a) 
   using F = Frag<T>;
   using TL = Tile<T, D>;
   constexpr int kSteps = D / F::kElems;
-  // double buffer: tile t+1 is in flight while tile t is consumed (deeper rings measured no faster)
+  // double buffer: tile t+1 is in flight while tile t is consumed (rings of three and four tiles
+  // measured no faster, and 4 % slower in the packed kernels)
   __shared__ __attribute__((aligned(1024))) char own_tiles[kPack ? 1024 : 2 * TL::kBytes];
 
   const WaveRole role = wave_role<kPack>(a);
