@@ -16,8 +16,9 @@
  *     (thread-local string, valid until the thread's next failing call).
  *   - "device" pointers are HIP device memory owned by the caller; "host" pointers are
  *     ordinary process memory owned by the caller.  The library never allocates or frees
- *     device memory and keeps no state between calls (the optional profiling events of
- *     cake_profile_enable aside).
+ *     device memory and keeps no state between calls (two documented exceptions: the optional
+ *     profiling events of cake_profile_enable and the fixed scratch array of
+ *     cake_decode_update_static).
  *   - Device work is enqueued on `stream` (a hipStream_t passed as void*; NULL = default
  *     stream) and the call returns without synchronising.  Host arrays are consumed before
  *     the call returns.  cake_cascade_allocate is host-only and synchronous.
