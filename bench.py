@@ -247,7 +247,7 @@ def main():
         if args.host_allocation:
             pref, hv = ev.preferences_to_host()
             budgets = ev.allocate(pref)
-            keep = np.minimum(np.maximum(budgets - ev.S_w, 0), ev.N_p)
+            keep = cake.cake_keep_counts(budgets, ev.N_p, ev.S_w)
             ev._carve_outputs(keep)
             kk = keep.reshape(-1).tolist()
             e[s][3].record()

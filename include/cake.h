@@ -214,7 +214,15 @@ int cake_layer_preference(const cake_shape* shape, const cake_params* params,
  *   pref     host [n_seen], finite and >= 0
  *   budgets  host [n_seen], written
  * Errors: NaN/negative preference, total_budget < n_seen*S_w, N <= S_w.
+ *
+ * cake_keep_counts (HOST) turns budgets into the number of prefix tokens each layer retains:
+ * the window tokens carry the score Omega in Sec. 4.3 Eq. 11 and are part of B_l, so
+ * keep[i] = clamp(budgets[i] - S_w, 0, cur_len[i]) for n entries (cur_len: the current
+ * evictable lengths, N - S_w before the first eviction).  These are the k of cake_select_topk
+ * and cake_compact_kv.
  */
+int cake_keep_counts(const int32_t* budgets, const int32_t* cur_len, int32_t n, int32_t window,
+                     int32_t* keep);
 int cake_cascade_allocate(const double* pref, int32_t n_seen, int64_t total_budget,
                           int32_t window, int32_t seq_len, int32_t* budgets);
 

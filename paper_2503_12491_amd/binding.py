@@ -116,6 +116,17 @@ def cake_layer_preference(shape, params, workspace, pref, hv=None, stream=None) 
                                         _stream(stream)))
 
 
+def cake_keep_counts(budgets, cur_len, window: int):
+    """Prefix tokens kept per entry; budgets and cur_len are integer arrays of one shape (returned shape too)."""
+    import numpy as np
+    b = np.ascontiguousarray(budgets, dtype=np.int32)
+    c = np.ascontiguousarray(np.broadcast_to(cur_len, b.shape), dtype=np.int32)
+    out = np.empty_like(b)
+    as_p = lambda a: a.ctypes.data_as(ctypes.POINTER(ctypes.c_int32))
+    _check(load().cake_keep_counts(as_p(b), as_p(c), b.size, window, as_p(out)))
+    return out.astype(np.int64)
+
+
 def cake_cascade_allocate(pref: Sequence[float], total_budget: int, window: int, seq_len: int) -> list:
     n = len(pref)
     p = (ctypes.c_double * n)(*[float(x) for x in pref])

@@ -99,6 +99,16 @@ static int64_t seats_above(double p, double lam, int32_t window, int32_t n) {
   return lo - window + 1;
 }
 
+extern "C" int cake_keep_counts(const int32_t* budgets, const int32_t* cur_len, int32_t n, int32_t window, int32_t* keep) {
+  CAKE_REQUIRE(budgets && cur_len && keep, "budgets, cur_len or keep is NULL");
+  CAKE_REQUIRE(n >= 0 && window >= 1, "n %d must be >= 0 and window %d >= 1", n, window);
+  for (int i = 0; i < n; ++i) {
+    CAKE_REQUIRE(cur_len[i] >= 0, "cur_len[%d] = %d is negative", i, cur_len[i]);
+    keep[i] = std::min(std::max(budgets[i] - window, 0), cur_len[i]);
+  }
+  return CAKE_OK;
+}
+
 extern "C" int cake_cascade_allocate(const double* pref, int32_t n_seen, int64_t total_budget,
                                      int32_t window, int32_t seq_len, int32_t* budgets) {
   CAKE_REQUIRE(pref != nullptr && budgets != nullptr, "pref or budgets is NULL");

@@ -180,7 +180,7 @@ class EvictionPass:
     def evict_launch(self, budgets: np.ndarray, stream=None):
         """Top-k and compaction for all layers; returns (keep, placement) without touching the
         outputs."""
-        keep = np.minimum(np.maximum(budgets - self.S_w, 0), self.N_p)
+        keep = C.cake_keep_counts(budgets, self.N_p, self.S_w)
         placement = self._carve_outputs(keep)
         kk = keep.reshape(-1).tolist()
         C.cake_select_topk(self.shape, self.tbl_ind, self._cur_full, kk, self.tbl_out[0], None, stream)
@@ -359,7 +359,7 @@ class CascadeSession:
             budgets[:, b] = C.cake_cascade_allocate(self.pref[b, : m + 1], self.total_budget, S_w, N)
         self.budgets = budgets
         self.stage_budgets.append(budgets.copy())
-        keep = np.minimum(np.maximum(budgets - S_w, 0), self.cur_len[: m + 1])
+        keep = C.cake_keep_counts(budgets, self.cur_len[: m + 1], S_w)
         layers = np.nonzero((keep < self.cur_len[: m + 1]).any(axis=1))[0].tolist()
         if not layers:
             return budgets

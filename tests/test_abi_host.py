@@ -141,3 +141,20 @@ def test_workspace_grows_with_the_problem(cake):
     n_p = 131072 - 64
     assert big >= 32 * 8 * n_p * 4          # at least the un-pooled indicator
     assert big < 400 * 2 ** 20
+
+
+def test_keep_counts_clamp_budget_minus_window(cake):
+    """cake_keep_counts: k = clamp(B_l - S_w, 0, cur_len), the count the oracle's evict() retains."""
+    from paper_2503_12491_amd import binding as C
+    budgets = np.array([[64, 100], [3000, 10], [65, 700]])
+    cur = np.array([[500, 20], [500, 0], [1, 636]])
+    got = C.cake_keep_counts(budgets, cur, 64)
+    assert got.tolist() == [[0, 20], [500, 0], [1, 636]]
+    assert C.cake_keep_counts(budgets, 1000, 64).tolist() == [[0, 36], [1000, 0], [1, 636]]
+    # the oracle keeps budget - window prefix rows when the budget includes the window
+    k = np.arange(40 * 3, dtype=np.float64).reshape(40, 3)
+    ind = np.linspace(1.0, 0.0, 32)
+    k_hat, _, _, idx = co.evict(k, k, ind, 8 + 5, 8)
+    assert k_hat.shape[0] == 13 and int(C.cake_keep_counts(np.array([13]), 32, 8)[0]) == idx.shape[0]
+    with pytest.raises(C.CakeError):
+        C.cake_keep_counts(np.array([5]), np.array([-1]), 4)
