@@ -849,8 +849,15 @@ int window_scores_impl(const cake_shape* shape, const cake_params* params,
                        ScoreParts parts = kPartsAll, int key_begin = 0, int key_count = 0) {
   if (int rc = check_shape_scores(shape)) return rc;
   CAKE_REQUIRE(params != nullptr, "params is NULL");
-  CAKE_REQUIRE(q_win && k && indicator, "q_win, k or indicator table is NULL");
-  CAKE_REQUIRE(q_strides && k_strides, "q_strides or k_strides is NULL");
+  // what the parts of this call touch: the two finishing steps read neither queries nor keys,
+  // and only the resident form and the pooling step write the indicator
+  const bool reads_keys = parts == kPartsAll || parts == kPartsPass1Segment || parts == kPartsPass2Segment;
+  const bool writes_indicator = parts == kPartsAll || parts == kPartsPool;
+  if (reads_keys) {
+    CAKE_REQUIRE(q_win && k, "q_win or k table is NULL");
+    CAKE_REQUIRE(q_strides && k_strides, "q_strides or k_strides is NULL");
+  }
+  CAKE_REQUIRE(!writes_indicator || indicator, "indicator table is NULL");
   CAKE_REQUIRE(params->pool_kernel >= 1 && params->pool_kernel % 2 == 1 && params->pool_kernel <= 2 * kPoolMaxHalf + 1,
                "pool_kernel %d must be odd and within [1, %d]", params->pool_kernel, 2 * kPoolMaxHalf + 1);
   CAKE_REQUIRE(params->indicator_mode >= CAKE_IND_MEAN_PLUS_VAR && params->indicator_mode <= CAKE_IND_CUMULATIVE,
@@ -858,12 +865,14 @@ int window_scores_impl(const cake_shape* shape, const cake_params* params,
   CAKE_REQUIRE(params->var_correction == 0 || params->var_correction == 1, "var_correction %d must be 0 or 1", params->var_correction);
   CAKE_REQUIRE(std::isfinite(params->gamma) && std::isfinite(params->scale) && params->scale >= 0.f, "gamma/scale must be finite, scale >= 0");
   const size_t eb = elem_bytes(shape->dtype);
-  for (int i = 0; i < 3; ++i) {
-    CAKE_REQUIRE(q_strides[i] >= 0 && k_strides[i] >= 0, "negative stride");
-    CAKE_REQUIRE((q_strides[i] * eb) % 16 == 0 && (k_strides[i] * eb) % 16 == 0, "strides must be multiples of 16 bytes");
+  if (reads_keys) {
+    for (int i = 0; i < 3; ++i) {
+      CAKE_REQUIRE(q_strides[i] >= 0 && k_strides[i] >= 0, "negative stride");
+      CAKE_REQUIRE((q_strides[i] * eb) % 16 == 0 && (k_strides[i] * eb) % 16 == 0, "strides must be multiples of 16 bytes");
+    }
+    CAKE_REQUIRE(q_strides[2] >= shape->head_dim && k_strides[2] >= shape->head_dim, "token stride below head_dim");
+    CAKE_REQUIRE(k_strides[2] * (int64_t)eb <= (int64_t)1 << 27, "key token stride above 128 MiB");
   }
-  CAKE_REQUIRE(q_strides[2] >= shape->head_dim && k_strides[2] >= shape->head_dim, "token stride below head_dim");
-  CAKE_REQUIRE(k_strides[2] * (int64_t)eb <= (int64_t)1 << 27, "key token stride above 128 MiB");
   const ScoreLayout lay = score_layout(*shape);
   if (workspace == nullptr || (reinterpret_cast<uintptr_t>(workspace) & 255) != 0)
     return fail(CAKE_ERR_WORKSPACE, "workspace is NULL or not 256-byte aligned");
@@ -873,7 +882,8 @@ int window_scores_impl(const cake_shape* shape, const cake_params* params,
 
   ScoreArgs a{};
   a.q_win = q_win; a.k = k; a.indicator = indicator;
-  for (int i = 0; i < 3; ++i) { a.qs[i] = q_strides[i]; a.ks[i] = k_strides[i]; }
+  if (reads_keys)
+    for (int i = 0; i < 3; ++i) { a.qs[i] = q_strides[i]; a.ks[i] = k_strides[i]; }
   a.batch = shape->batch; a.h_kv = shape->n_kv_heads; a.group = shape->n_q_heads / shape->n_kv_heads;
   a.n = shape->seq_len; a.n_p = shape->seq_len - shape->window;
   a.chunk = lay.chunk; a.n_chunks = lay.n_chunks; a.n_chunks_p = lay.n_chunks_p; a.pool = params->pool_kernel;
@@ -958,20 +968,15 @@ extern "C" int cake_window_scores_segment(const cake_shape* shape, const cake_pa
                                           const int64_t* q_strides, const int64_t* k_strides,
                                           void* workspace, size_t workspace_bytes, void* stream) {
   CAKE_REQUIRE(pass == 1 || pass == 2, "pass %d must be 1 or 2", pass);
-  float* const* no_indicator = reinterpret_cast<float* const*>(workspace);    // not dereferenced by the segment kernels
-  return window_scores_impl(shape, params, q_win, k_segment, q_strides, k_strides, nullptr, no_indicator, workspace,
+  return window_scores_impl(shape, params, q_win, k_segment, q_strides, k_strides, nullptr, nullptr, workspace,
                             workspace_bytes, stream, pass == 1 ? kPartsPass1Segment : kPartsPass2Segment, key_begin, key_count);
 }
 
 extern "C" int cake_window_scores_finish(const cake_shape* shape, const cake_params* params, int32_t pass,
                                          float* const* indicator, void* workspace, size_t workspace_bytes, void* stream) {
   CAKE_REQUIRE(pass == 1 || pass == 2, "pass %d must be 1 or 2", pass);
-  CAKE_REQUIRE(pass == 1 || indicator != nullptr, "indicator table is NULL");
-  static const int64_t unit[3] = {256, 256, 256};     // placeholders: these two kernels read neither q nor k
-  const void* const* none = reinterpret_cast<const void* const*>(workspace);
-  float* const* ind = pass == 2 ? indicator : reinterpret_cast<float* const*>(workspace);
-  return window_scores_impl(shape, params, none, none, unit, unit, nullptr, ind, workspace, workspace_bytes, stream,
-                            pass == 1 ? kPartsCombine : kPartsPool);
+  return window_scores_impl(shape, params, nullptr, nullptr, nullptr, nullptr, nullptr, indicator, workspace,
+                            workspace_bytes, stream, pass == 1 ? kPartsCombine : kPartsPool);
 }
 
 extern "C" int cake_layer_preference(const cake_shape* shape, const cake_params* params,

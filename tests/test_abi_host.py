@@ -158,3 +158,35 @@ def test_keep_counts_clamp_budget_minus_window(cake):
     assert k_hat.shape[0] == 13 and int(C.cake_keep_counts(np.array([13]), 32, 8)[0]) == idx.shape[0]
     with pytest.raises(C.CakeError):
         C.cake_keep_counts(np.array([5]), np.array([-1]), 4)
+
+
+def test_segment_calls_reject_bad_arguments_on_the_host(cake):
+    """cake_window_scores_segment / _finish validate before anything is launched: pass number,
+    segment alignment to the chunk of cake_scores_chunk_keys, range, NULL tables, workspace."""
+    from paper_2503_12491_amd import binding as C
+    import torch
+    shape = C.make_shape(1, 2, 4, 2, 64, 1024 + 77, 32, torch.float32)
+    params = C.make_params()
+    chunk = C.cake_scores_chunk_keys(shape)
+    assert chunk == 256
+    assert C.cake_scores_chunk_keys(C.make_shape(1, 1, 32, 8, 128, 131072, 64, torch.bfloat16)) == 2048
+    lib = C.load()
+    one = (ctypes.c_int64 * 3)(4096, 1024, 64)
+    tbl = ctypes.c_void_p(256)            # never dereferenced: every call below fails validation first
+    ws = ctypes.c_void_p(1 << 20)
+
+    def seg(which, lo, cnt, q=tbl, k=tbl, wsp=ws, nbytes=1 << 30):
+        return lib.cake_window_scores_segment(ctypes.byref(shape), ctypes.byref(params), which, lo, cnt, q, k, one, one,
+                                              wsp, nbytes, None)
+    assert seg(3, 0, chunk) == -1 and b"pass" in lib.cake_last_error()
+    assert seg(1, chunk // 2, chunk) == -1 and b"multiple of the chunk" in lib.cake_last_error()
+    assert seg(1, 0, chunk + 1) == -1
+    assert seg(2, 0, 0) == -1
+    assert seg(1, chunk, 1024 + 77) == -1                 # runs past seq_len
+    assert seg(1, 0, chunk, q=None) == -1
+    assert seg(1, 0, chunk, nbytes=16) == -3
+    assert seg(1, 0, chunk, wsp=None) == -3
+    fin = lib.cake_window_scores_finish
+    assert fin(ctypes.byref(shape), ctypes.byref(params), 0, tbl, ws, 1 << 30, None) == -1
+    assert fin(ctypes.byref(shape), ctypes.byref(params), 2, None, ws, 1 << 30, None) == -1
+    assert fin(ctypes.byref(shape), ctypes.byref(params), 1, None, ws, 16, None) == -3
