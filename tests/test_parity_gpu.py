@@ -165,6 +165,22 @@ def test_scores_bf16_ragged_chunks(cake):
     _check_scores(cake, cfg)
 
 
+@pytest.mark.parametrize("h_q,h_kv,d,layers,batch", [
+    (10, 2, 128, 1, 1),      # G = 5: two slices in a workgroup of three (one repeats the last slice, stores nothing)
+    (20, 4, 64, 1, 1),       # G = 5, d = 64: four slices, two workgroups
+    (12, 2, 128, 2, 1),      # G = 6: two slices per workgroup, exactly filled
+    (18, 3, 64, 1, 3),       # G = 6, d = 64, batch of 3: nine slices, the last workgroup half empty
+])
+def test_scores_packed_workgroups_for_groups_of_5_and_6(cake, h_q, h_kv, d, layers, batch):
+    """bf16 S_w = 32 kernels that put several (layer, sequence, KV head) slices in one workgroup:
+    slice counts that do and do not fill the last workgroup, ragged chunk ends, the tail path."""
+    say(f"scores packed H_q={h_q} H_kv={h_kv} d={d} L={layers} B={batch}")
+    cfg = CONFIGS[2].scaled(n_q_heads=h_q, n_kv_heads=h_kv, head_dim=d, n_layers=layers, batch=batch,
+                            seq_len=512 + 32 + 45, total_budget=layers * 200)
+    _check_scores(cake, cfg)
+    _check_scores(cake, cfg, cake.make_params(indicator_mode=cake.CAKE_IND_VAR, pool_kernel=3))
+
+
 def test_scores_window64_and_drifting_heavy_hitters(cake):
     say("scores S_w=64 / drift")
     cfg = CONFIGS[3].scaled(n_layers=2, seq_len=4096 + 64 + 5, window=64, total_budget=2 * 400)
