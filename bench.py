@@ -131,6 +131,23 @@ def decode_bench(cake, cfg, ev, steps, warmup):
         wall = (time.perf_counter() - t0) / steps
         out[name] = {"us_per_layer_stream": e0.elapsed_time(e1) / steps / L * 1e3, "us_per_layer_wall": wall / L * 1e6,
                      "ms_per_token_wall": wall * 1e3}
+    # all layers in one call, for a caller that keeps the token's projections until its forward pass is over
+    cache = cake.DecodeSlots(res, cfg.n_q_heads, cfg.window)
+    q_all = qn[None].expand(L, -1, -1, -1).contiguous()
+    k_all = kn[None].expand(L, -1, -1, -1).contiguous()
+    for _ in range(warmup):
+        cache.step_all(q_all, k_all, k_all)
+    torch.cuda.synchronize()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    t0 = time.perf_counter()
+    e0.record()
+    for _ in range(steps):
+        cache.step_all(q_all, k_all, k_all)
+    e1.record()
+    torch.cuda.synchronize()
+    wall = (time.perf_counter() - t0) / steps
+    out["in_place_all_layers_one_call"] = {"us_per_layer_stream": e0.elapsed_time(e1) / steps / L * 1e3,
+                                           "us_per_layer_wall": wall / L * 1e6, "ms_per_token_wall": wall * 1e3}
     print(json.dumps({"metric": "decode cache maintenance per generated token", "unit": "us per layer", "n_gpus": 1,
                       "value": out["in_place_step"]["us_per_layer_stream"], "higher_is_better": False, "steps": steps,
                       "warmup": warmup, "dtype": cfg.dtype, "data": "synthetic",

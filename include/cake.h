@@ -350,8 +350,8 @@ int cake_decode_update(const cake_shape* shape, const cake_params* params,
  *   shape      seq_len >= max over layers of cap + S_w + 1 (sizes the workspace)
  *   q_new      device [n_layers, B, H_q, d], element strides q_strides (host [3]: layer, batch, head)
  *   k_new, v_new  device [n_layers, B, H_kv, d], element strides kv_new_strides (host [3])
- *   k_slots, v_slots  tables; [B, H_kv, cap_l + S_w + 1, d], element strides slot_strides
- *              (host [3]: batch, head, slot; the same for every layer of the call), updated
+ *   k_slots, v_slots  tables; [B, H_kv, cap_l + S_w + 1, d], element strides slot_strides[l]
+ *              (host [n_layers][3]: batch, head, slot of every layer), updated
  *   indicator  table; indicator[l] -> [B, H_kv, cap_l + 1] f32 in logical order, updated
  *   order      table; order[l] -> [B, H_kv, cap_l + S_w + 1] int32, updated
  *   state      table; state[l] -> [B, H_kv, 4] int32: {cur, free slot, logical index of the row

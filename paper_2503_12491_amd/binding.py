@@ -187,8 +187,10 @@ def cake_decode_step_workspace_bytes(shape: cake_shape) -> int:
 
 def cake_decode_step(shape, params, q_new, q_strides, k_new, v_new, kv_new_strides, k_slots, v_slots, slot_strides,
                      indicator, order, state, cap, workspace, stream=None) -> None:
+    """slot_strides: one [batch, head, slot] triple per layer of the call."""
+    flat = [s for layer in slot_strides for s in layer]
     _check(load().cake_decode_step(ctypes.byref(shape), ctypes.byref(params), _ptr(q_new), _i64(q_strides), _ptr(k_new),
-                                   _ptr(v_new), _i64(kv_new_strides), _ptr(k_slots), _ptr(v_slots), _i64(slot_strides),
+                                   _ptr(v_new), _i64(kv_new_strides), _ptr(k_slots), _ptr(v_slots), _i64(flat),
                                    _ptr(indicator), _ptr(order), _ptr(state), _i32(cap), _ptr(workspace),
                                    workspace.numel() * workspace.element_size(), _stream(stream)))
 

@@ -196,7 +196,8 @@ struct StepArgs {
   const void* q_new; const void* k_new; const void* v_new;
   void* const* k_slots; void* const* v_slots;
   float* const* indicator; int32_t* const* order; int32_t* const* state;
-  int64_t qs[3], ns[3], ss[3];      // element strides: q_new / k_new,v_new (layer, batch, head); slots (batch, head, slot)
+  int64_t qs[3], ns[3];             // element strides of q_new / k_new, v_new: layer, batch, head
+  int64_t ss[kMaxLaunchLayers][3];  // element strides of every layer's slots: batch, head, slot
   int32_t batch, h_kv, group, window, pool, n_chunks, rows_max;
   float c, inv_g;
   float* logits;      // [slice][rows_max][kMaxGroup]
@@ -221,7 +222,7 @@ __global__ __launch_bounds__(kThreads) void step_logits_kernel(StepArgs a) {
   const int cap = a.cap[ll];
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const T* q = reinterpret_cast<const T*>(a.q_new) + ll * a.qs[0] + b * a.qs[1] + (int64_t)(g * a.group) * a.qs[2];
-  T* ks = reinterpret_cast<T*>(a.k_slots[ll]) + b * a.ss[0] + g * a.ss[1];
+  T* ks = reinterpret_cast<T*>(a.k_slots[ll]) + b * a.ss[ll][0] + g * a.ss[ll][1];
   int32_t* order = a.order[ll] + ((int64_t)b * a.h_kv + g) * (cap + a.window + 1);
   for (int i = tid; i < a.group * D; i += kThreads) q_lds[i] = (float)q[(i / D) * a.qs[2] + (i % D)];
   __syncthreads();
@@ -237,8 +238,8 @@ __global__ __launch_bounds__(kThreads) void step_logits_kernel(StepArgs a) {
       // predecessor in the scored part (the row that just left the window) at indicator 0
       const T* kn = reinterpret_cast<const T*>(a.k_new) + ll * a.ns[0] + b * a.ns[1] + g * a.ns[2];
       const T* vn = reinterpret_cast<const T*>(a.v_new) + ll * a.ns[0] + b * a.ns[1] + g * a.ns[2];
-      T* kd = ks + free_slot * a.ss[2];
-      T* vd = reinterpret_cast<T*>(a.v_slots[ll]) + b * a.ss[0] + g * a.ss[1] + free_slot * a.ss[2];
+      T* kd = ks + free_slot * a.ss[ll][2];
+      T* vd = reinterpret_cast<T*>(a.v_slots[ll]) + b * a.ss[ll][0] + g * a.ss[ll][1] + free_slot * a.ss[ll][2];
       for (int e = 0; e < D; e += 16 / (int)sizeof(T)) {
         *reinterpret_cast<uint4*>(kd + e) = *reinterpret_cast<const uint4*>(kn + e);
         *reinterpret_cast<uint4*>(vd + e) = *reinterpret_cast<const uint4*>(vn + e);
@@ -247,7 +248,7 @@ __global__ __launch_bounds__(kThreads) void step_logits_kernel(StepArgs a) {
       a.indicator[ll][((int64_t)b * a.h_kv + g) * (cap + 1) + cur] = 0.f;
       row = kn;
     } else {
-      row = ks + order[j] * a.ss[2];
+      row = ks + order[j] * a.ss[ll][2];
     }
     row_logits<T, D>(row, q_lds, a.group, a.c, m);
     float* lg = a.logits + (slice * a.rows_max + j) * kMaxGroup;
@@ -569,9 +570,12 @@ extern "C" int cake_decode_step(const cake_shape* shape, const cake_params* para
   CAKE_REQUIRE(L <= kMaxLaunchLayers, "at most %d layers per cake_decode_step call", kMaxLaunchLayers);
   const size_t eb = elem_bytes(shape->dtype);
   for (int i = 0; i < 3; ++i) {
-    CAKE_REQUIRE(q_strides[i] >= 0 && kv_new_strides[i] >= 0 && slot_strides[i] >= 0, "negative stride");
-    CAKE_REQUIRE((q_strides[i] * eb) % 16 == 0 && (kv_new_strides[i] * eb) % 16 == 0 && (slot_strides[i] * eb) % 16 == 0,
-                 "strides must be multiples of 16 bytes");
+    CAKE_REQUIRE(q_strides[i] >= 0 && kv_new_strides[i] >= 0, "negative stride");
+    CAKE_REQUIRE((q_strides[i] * eb) % 16 == 0 && (kv_new_strides[i] * eb) % 16 == 0, "strides must be multiples of 16 bytes");
+  }
+  for (int i = 0; i < 3 * L; ++i) {
+    CAKE_REQUIRE(slot_strides[i] >= 0, "negative stride");
+    CAKE_REQUIRE((slot_strides[i] * eb) % 16 == 0, "strides must be multiples of 16 bytes");
   }
   for (int l = 0; l < L; ++l)
     CAKE_REQUIRE(cap[l] >= 0 && cap[l] + shape->window + 1 <= shape->seq_len,
@@ -585,7 +589,9 @@ extern "C" int cake_decode_step(const cake_shape* shape, const cake_params* para
   StepArgs a{};
   a.q_new = q_new; a.k_new = k_new; a.v_new = v_new;
   a.k_slots = k_slots; a.v_slots = v_slots; a.indicator = indicator; a.order = order; a.state = state;
-  for (int i = 0; i < 3; ++i) { a.qs[i] = q_strides[i]; a.ns[i] = kv_new_strides[i]; a.ss[i] = slot_strides[i]; }
+  for (int i = 0; i < 3; ++i) { a.qs[i] = q_strides[i]; a.ns[i] = kv_new_strides[i]; }
+  for (int l = 0; l < L; ++l)
+    for (int i = 0; i < 3; ++i) a.ss[l][i] = slot_strides[l * 3 + i];
   a.batch = B; a.h_kv = shape->n_kv_heads; a.group = G; a.window = shape->window; a.pool = params->pool_kernel;
   a.rows_max = shape->seq_len;
   a.n_chunks = (shape->seq_len + kThreads - 1) / kThreads;

@@ -548,6 +548,7 @@ class DecodeSlots:
         self.shape1 = C.make_shape(self.B, 1, self.H_q, self.H_kv, self.d, rows_max, self.S_w, self.dtype)
         self.ws = torch.empty(C.cake_decode_step_workspace_bytes(self.shape1), dtype=torch.uint8, device=dev)
         self.slot_strides = [_strides3(t) for t in self.k]
+        self._ws_all = None
 
     def step(self, layer: int, q_new: torch.Tensor, k_new: torch.Tensor, v_new: torch.Tensor) -> None:
         """q_new [B, H_q, d]; k_new, v_new [B, H_kv, d]: the generated token's projections at `layer`."""
@@ -555,8 +556,29 @@ class DecodeSlots:
         assert q_new.stride(2) == 1 and k_new.stride(2) == 1 and v_new.stride() == k_new.stride()
         C.cake_decode_step(self.shape1, self.params, q_new, [0, q_new.stride(0), q_new.stride(1)], k_new, v_new,
                            [0, k_new.stride(0), k_new.stride(1)], self.tbl["k"][l:l + 1], self.tbl["v"][l:l + 1],
-                           self.slot_strides[l], self.tbl["ind"][l:l + 1], self.tbl["order"][l:l + 1],
+                           [self.slot_strides[l]], self.tbl["ind"][l:l + 1], self.tbl["order"][l:l + 1],
                            self.tbl["state"][l:l + 1], [self.cap[l]], self.ws)
+
+    def step_all(self, q_new: torch.Tensor, k_new: torch.Tensor, v_new: torch.Tensor) -> None:
+        """The maintenance of one generated token for every layer in one call per 32 layers, for a
+        caller that keeps the token's projections of all layers until its forward pass is over.
+        q_new [L, B, H_q, d]; k_new, v_new [L, B, H_kv, d].  Same result as `step` layer by layer."""
+        assert q_new.stride(3) == 1 and k_new.stride(3) == 1 and v_new.stride() == k_new.stride()
+        per_call = 32
+        if self._ws_all is None:
+            n = min(per_call, self.L)
+            self._shape_all = C.make_shape(self.B, n, self.H_q, self.H_kv, self.d, max(self.cap) + self.S_w + 1, self.S_w,
+                                           self.dtype)
+            self._ws_all = torch.empty(C.cake_decode_step_workspace_bytes(self._shape_all), dtype=torch.uint8,
+                                       device=self.ws.device)
+        for l0 in range(0, self.L, per_call):
+            l1 = min(l0 + per_call, self.L)
+            shape = self._shape_all if l1 - l0 == self._shape_all.n_layers else C.make_shape(
+                self.B, l1 - l0, self.H_q, self.H_kv, self.d, max(self.cap) + self.S_w + 1, self.S_w, self.dtype)
+            C.cake_decode_step(shape, self.params, q_new[l0:l1], list(q_new.stride()[:3]), k_new[l0:l1], v_new[l0:l1],
+                               list(k_new.stride()[:3]), self.tbl["k"][l0:l1], self.tbl["v"][l0:l1],
+                               self.slot_strides[l0:l1], self.tbl["ind"][l0:l1], self.tbl["order"][l0:l1],
+                               self.tbl["state"][l0:l1], self.cap[l0:l1], self._ws_all)
 
     def logical(self, layer: int, b: int):
         """(K, V [H_kv, cur + S_w, d], indicator [H_kv, cur], evicted logical index [H_kv]) of one

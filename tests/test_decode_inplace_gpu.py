@@ -76,3 +76,29 @@ def test_in_place_steps_match_the_oracle_ragged_batch(cake):
 def test_in_place_steps_match_the_oracle_fp32_tiny(cake):
     say("in-place decode: tiny fp32 config")
     _check_steps(cake, CONFIGS[1], n_steps=4, seed=7)
+
+
+def test_all_layers_in_one_call_equal_layer_by_layer(cake):
+    """DecodeSlots.step_all (one cake_decode_step call for all layers, per-layer slot strides and
+    capacities) leaves every buffer exactly as the layer-by-layer steps do."""
+    say("in-place decode: all layers in one call vs layer by layer")
+    cfg = CONFIGS[2].scaled(n_layers=5, seq_len=1500, total_budget=5 * 260)
+    inp = make_config_inputs(cfg, device=DEV)
+    L, B = cfg.n_layers, cfg.batch
+    res = cake.EvictionPass([inp["q_win"][l] for l in range(L)], [inp["k"][l] for l in range(L)],
+                            [inp["v"][l] for l in range(L)], cfg.total_budget).run()
+    torch.cuda.synchronize()
+    assert len(set(int(x) for x in res.keep[:, 0])) > 1                  # layers of different capacities
+    one, many = cake.DecodeSlots(res, cfg.n_q_heads, cfg.window), cake.DecodeSlots(res, cfg.n_q_heads, cfg.window)
+    gen = torch.Generator().manual_seed(3)
+    for step in range(4):
+        qn = (torch.randn(L, B, cfg.n_q_heads, cfg.head_dim, generator=gen) * 2).to(cfg.torch_dtype).to(DEV)
+        kn = torch.randn(L, B, cfg.n_kv_heads, cfg.head_dim, generator=gen).to(cfg.torch_dtype).to(DEV)
+        vn = torch.randn(L, B, cfg.n_kv_heads, cfg.head_dim, generator=gen).to(cfg.torch_dtype).to(DEV)
+        for l in range(L):
+            one.step(l, qn[l], kn[l], vn[l])
+        many.step_all(qn, kn, vn)
+        torch.cuda.synchronize()
+        for l in range(L):
+            for name in ("k", "v", "ind", "order", "state"):
+                assert torch.equal(getattr(one, name)[l], getattr(many, name)[l]), (step, l, name)
