@@ -44,6 +44,9 @@ def parse_args():
     ap.add_argument("--decode", action="store_true",
                     help="instead of the prefill pass: time the decode-phase cache maintenance of one generated token "
                          "over all layers (in-place step, and the append + compaction form beside it)")
+    ap.add_argument("--cascade", action="store_true",
+                    help="instead of the one-shot pass: Alg. 1 stage by stage (every admitted layer scored alone, all "
+                         "earlier layers re-evicted to their new budgets), same final caches by Thm. 2")
     ap.add_argument("--host-allocation", action="store_true",
                     help="variant: budgets on the host (cake_cascade_allocate) between the scores and EVICT")
     return ap.parse_args()
@@ -209,6 +212,21 @@ def main():
 
     if args.decode:
         decode_bench(cake, cfg, ev, args.steps, args.warmup)
+        return
+    if args.cascade:
+        for _ in range(args.warmup):
+            ev.run_cascade(track_positions=False)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(args.steps):
+            ev.run_cascade(track_positions=False)
+        torch.cuda.synchronize()
+        ms = (time.perf_counter() - t0) / args.steps * 1e3
+        print(json.dumps({"metric": f"prefix tokens*layers/s evicted (config {cfg.cid}, cascade mode)",
+                          "value": B * cfg.seq_len * L / (ms * 1e-3), "unit": "tokens*layers/s", "n_gpus": 1,
+                          "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms, "higher_is_better": True,
+                          "dtype": cfg.dtype, "data": "synthetic",
+                          "config": {"workload": f"config {cfg.cid} ({cfg.name}): Alg. 1 in {L} stages"}}))
         return
 
     if args.copy_calibration:

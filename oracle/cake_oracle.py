@@ -27,12 +27,20 @@ Readings taken where the paper is silent (each also listed in the design notes):
   * top-k breaks ties towards the lower position and returns ascending positions;
   * in the decoding phase the pooled attention row of the new token is added to the stored
     indicator (the paper names `update_score` without defining it) and the row that leaves the
-    window starts from 0.
+    window starts from 0;
+  * the quantised form of the retained cache (appendix on compatibility with quantisation
+    methods, which combines the method with a 4-bit key-per-channel / value-per-token
+    quantiser) is asymmetric uniform b-bit quantisation over groups of 32: keys per channel
+    over 32 consecutive retained tokens, values per token over 32 consecutive channels; the
+    window rows stay as they are.  Scales and codes are formed in float32, the precision in
+    which the library decides them (a code is an integer decided by floating point).
 
 Pins (tests/test_oracle_pins.py): a hand-derived rational worked example,
 closed forms for uniform attention, zero temporal variance under static
 attention, library softmax / variance / max-pool / sort on special cases,
-brute-force apportionment and top-k, Proposition 1 and Theorem 2.
+brute-force apportionment and top-k, Proposition 1 and Theorem 2; for the quantiser
+exact reproduction of values on the grid, the half-step error bound, a brute-force
+nearest-level search and the key/value group orientation.
 """
 from __future__ import annotations
 
@@ -351,3 +359,49 @@ def decode_step(q_new, cache: dict, k_new, v_new, window: int, p: OracleParams) 
         out["v"].append(compact(v[g], sel, window))
         out["ind"].append(ind[g][sel])
     return {"k": np.stack(out["k"]), "v": np.stack(out["v"]), "ind": np.stack(out["ind"]), "idx": np.stack(out["idx"])}
+
+
+# ----------------------------------------------------------------------------------------
+# Quantised storage of the retained cache (appendix "Comparison and compatibility with
+# quantization methods": eviction combined with key-per-channel / value-per-token quantisation)
+# ----------------------------------------------------------------------------------------
+QUANT_GROUP = 32
+
+
+def quantize_uniform(x: np.ndarray, bits: int, axis: int, group: int = QUANT_GROUP):
+    """Asymmetric uniform quantisation to `bits` bits over groups of `group` consecutive entries
+    along `axis` (the last group may be shorter): zero = group minimum, scale = (max - min) /
+    (2^bits - 1), code = round-half-even((x - zero) / scale) in [0, 2^bits - 1]; a constant group
+    has scale 0 and codes 0.  float32 throughout.  Returns (codes uint8 like x, scale, zero) with
+    the group index in place of `axis`."""
+    x = np.moveaxis(np.asarray(x, dtype=np.float32), axis, -1)
+    levels = np.float32(2 ** bits - 1)
+    n = x.shape[-1]
+    n_groups = -(-n // group)
+    codes = np.zeros(x.shape, dtype=np.uint8)
+    scale = np.zeros(x.shape[:-1] + (n_groups,), dtype=np.float32)
+    zero = np.zeros_like(scale)
+    for gi in range(n_groups):
+        seg = x[..., gi * group:(gi + 1) * group]
+        lo, hi = seg.min(axis=-1), seg.max(axis=-1)
+        sc = ((hi - lo) / levels).astype(np.float32)
+        with np.errstate(divide="ignore", invalid="ignore"):
+            c = np.rint(((seg - lo[..., None]).astype(np.float32) / sc[..., None]).astype(np.float32))
+        c = np.where(sc[..., None] > 0, np.clip(c, 0, levels), 0)
+        codes[..., gi * group:(gi + 1) * group] = c.astype(np.uint8)
+        scale[..., gi], zero[..., gi] = sc, lo
+    return np.moveaxis(codes, -1, axis), np.moveaxis(scale, -1, axis), np.moveaxis(zero, -1, axis)
+
+
+def dequantize_uniform(codes: np.ndarray, scale: np.ndarray, zero: np.ndarray, axis: int, group: int = QUANT_GROUP):
+    """x ~ zero + code * scale with each group's scale and zero spread over its entries."""
+    n = codes.shape[axis]
+    rep = lambda a: np.repeat(a, group, axis=axis).take(np.arange(n), axis=axis)
+    return rep(zero).astype(np.float64) + codes.astype(np.float64) * rep(scale).astype(np.float64)
+
+
+def quantize_cache(k_rows: np.ndarray, v_rows: np.ndarray, bits: int):
+    """The retained prefix rows of one head, k_rows / v_rows [keep, d]: keys per channel over
+    groups of 32 tokens (scale, zero [ceil(keep/32), d]), values per token over groups of 32
+    channels (scale, zero [keep, d/32])."""
+    return quantize_uniform(k_rows, bits, axis=0), quantize_uniform(v_rows, bits, axis=1)

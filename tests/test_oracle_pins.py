@@ -498,3 +498,82 @@ def test_decode_step_keeps_the_size_and_evicts_the_lowest():
     q = np.zeros((h_q, d)); q[:] = 10.0 * cache["k"][0, cur]                  # ... and the query points at it
     out = co.decode_step(q, cache, k_new, v_new, w, p)
     assert cur in out["idx"][0] and 0 not in out["idx"][0]
+
+
+# ---------------------------------------------------------------------------------------------
+# Quantised storage of the retained cache (appendix on compatibility with quantisation methods)
+# ---------------------------------------------------------------------------------------------
+@pytest.mark.parametrize("bits", [2, 4, 8])
+def test_quantiser_reproduces_grid_values_and_stays_within_half_a_step(bits):
+    """Values that already lie on a b-bit grid come back exactly with the codes that built them;
+    arbitrary values come back within half a step (plus float32 rounding); codes stay in range;
+    a constant group has scale 0, codes 0 and is reproduced exactly."""
+    rng = np.random.default_rng(bits)
+    levels = 2 ** bits - 1
+    codes_in = rng.integers(0, levels + 1, size=(64, 5))
+    codes_in[0, :], codes_in[1, :] = 0, levels                      # both ends present in every group of column values
+    codes_in[32, :], codes_in[33, :] = 0, levels
+    lo, step = np.array([-3.0, 0.5, 10.0, -0.25, 0.0]), np.array([0.5, 0.25, 2.0, 0.125, 1.0])   # exact in float32
+    x = lo + codes_in * step
+    codes, scale, zero = co.quantize_uniform(x, bits, axis=0)
+    np.testing.assert_array_equal(codes, codes_in)
+    np.testing.assert_array_equal(zero, np.broadcast_to(lo.astype(np.float32), (2, 5)))
+    np.testing.assert_allclose(scale, np.broadcast_to(step, (2, 5)), rtol=1e-6)
+    np.testing.assert_allclose(co.dequantize_uniform(codes, scale, zero, 0), x, rtol=1e-6, atol=1e-6)
+    y = rng.standard_normal((100, 70)) * 3
+    for axis in (0, 1):
+        c, s, z = co.quantize_uniform(y, bits, axis=axis)
+        assert c.dtype == np.uint8 and c.max() <= levels
+        assert s.shape[axis] == -(-y.shape[axis] // 32) and s.shape[1 - axis] == y.shape[1 - axis]
+        back = co.dequantize_uniform(c, s, z, axis)
+        half = np.repeat(s, 32, axis=axis).take(np.arange(y.shape[axis]), axis=axis) / 2
+        assert np.all(np.abs(back - y.astype(np.float32)) <= half * (1 + 1e-5) + 1e-6)
+    const = np.full((40, 3), 1.75)
+    c, s, z = co.quantize_uniform(const, bits, axis=0)
+    assert not c.any() and not s.any() and np.all(z == 1.75)
+    np.testing.assert_array_equal(co.dequantize_uniform(c, s, z, 0), const)
+
+
+def test_quantiser_codes_are_the_nearest_levels_by_brute_force():
+    """Every code is the level nearest to its value among all 2^b levels of its group (searched
+    exhaustively in float64; values within 1e-6 of a step's midpoint are left out)."""
+    rng = np.random.default_rng(5)
+    x = (rng.standard_normal((45, 6)) * 2).astype(np.float32)
+    for bits in (2, 4):
+        c, s, z = co.quantize_uniform(x, bits, axis=0)
+        for col in range(x.shape[1]):
+            for r in range(x.shape[0]):
+                g = r // 32
+                grid = float(z[g, col]) + np.arange(2 ** bits) * float(s[g, col])
+                d = np.abs(grid - float(x[r, col]))
+                best = int(np.argmin(d))
+                if np.sort(d)[1] - np.sort(d)[0] > 1e-6:
+                    assert c[r, col] == best, (bits, r, col)
+
+
+def test_quantiser_groups_keys_by_channel_and_values_by_token():
+    """Orientation of the two quantisers.  Rows that are all equal (every token the same vector):
+    each key channel is constant over tokens, so keys come back exactly, while a value row still
+    spreads over its channels and is quantised.  Columns that are all equal (every channel the
+    same per token): the other way round.  And a change outside a group leaves the group alone."""
+    rng = np.random.default_rng(9)
+    row = rng.standard_normal(64).astype(np.float32)
+    same_rows = np.tile(row, (50, 1))
+    (kc, ks, kz), (vc, vs, vz) = co.quantize_cache(same_rows, same_rows, 4)
+    assert ks.shape == (2, 64) and vs.shape == (50, 2)
+    assert not ks.any() and np.array_equal(co.dequantize_uniform(kc, ks, kz, 0), same_rows)
+    assert vs.all() and np.abs(co.dequantize_uniform(vc, vs, vz, 1) - same_rows).max() > 1e-3
+    col = rng.standard_normal(50).astype(np.float32)
+    same_cols = np.tile(col[:, None], (1, 64))
+    (kc, ks, kz), (vc, vs, vz) = co.quantize_cache(same_cols, same_cols, 4)
+    assert not vs.any() and np.array_equal(co.dequantize_uniform(vc, vs, vz, 1), same_cols)
+    assert ks.all()
+    x = rng.standard_normal((70, 64)).astype(np.float32)
+    y = x.copy()
+    y[40, 5] += 100.0                                               # token group 1, channel 5 / channel group 0 of token 40
+    (kc0, _, _), (vc0, _, _) = co.quantize_cache(x, x, 4)
+    (kc1, _, _), (vc1, _, _) = co.quantize_cache(y, y, 4)
+    changed_k = np.argwhere(kc0 != kc1)
+    assert set(map(tuple, changed_k)) <= {(r, 5) for r in range(32, 64)}
+    changed_v = np.argwhere(vc0 != vc1)
+    assert set(map(tuple, changed_v)) <= {(40, c) for c in range(0, 32)}
