@@ -44,6 +44,9 @@ def parse_args():
     ap.add_argument("--decode", action="store_true",
                     help="instead of the prefill pass: time the decode-phase cache maintenance of one generated token "
                          "over all layers (in-place step, and the append + compaction form beside it)")
+    ap.add_argument("--quantize", type=int, default=0, metavar="BITS",
+                    help="instead of the pass: after one pass, time the 2/4/8-bit storage of the retained rows "
+                         "(cake_quantize_kv)")
     ap.add_argument("--cascade", action="store_true",
                     help="instead of the one-shot pass: Alg. 1 stage by stage (every admitted layer scored alone, all "
                          "earlier layers re-evicted to their new budgets), same final caches by Thm. 2")
@@ -212,6 +215,33 @@ def main():
 
     if args.decode:
         decode_bench(cake, cfg, ev, args.steps, args.warmup)
+        return
+    if args.quantize:
+        res = ev.run()
+        torch.cuda.synchronize()
+        quant = cake.CacheQuantizer(res, cfg.window, args.quantize)
+        for _ in range(args.warmup):
+            quant.run()
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(args.steps):
+            quant.run()
+        e1.record()
+        torch.cuda.synchronize()
+        ms = e0.elapsed_time(e1) / args.steps
+        rows = int(res.keep.sum()) * cfg.n_kv_heads
+        eb = 2 if cfg.dtype == "bf16" else 4
+        read_b = rows * cfg.head_dim * eb * 2
+        write_b = rows * (cfg.head_dim * args.quantize // 8) * 2 + rows * (cfg.head_dim // 32) * 8 + \
+            sum(-(-int(k) // 32) for k in res.keep.reshape(-1)) * cfg.n_kv_heads * cfg.head_dim * 8
+        print(json.dumps({"metric": f"retained rows quantised to {args.quantize} bits", "value": rows / (ms * 1e-3),
+                          "unit": "rows/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms,
+                          "higher_is_better": True, "dtype": cfg.dtype, "data": "synthetic",
+                          "config": {"workload": f"config {cfg.cid} ({cfg.name}): {rows} retained (head, row) pairs after one pass"},
+                          "roofline": {"kernel": "quantize_kv", "bound": "hbm", "achieved": (read_b + write_b) / (ms * 1e-3) / 1e9,
+                                       "peak": HBM_PEAK_GBPS, "unit": "GB/s",
+                                       "frac": (read_b + write_b) / (ms * 1e-3) / 1e9 / HBM_PEAK_GBPS, "traffic": None}}))
         return
     if args.cascade:
         for _ in range(args.warmup):

@@ -304,6 +304,33 @@ int cake_evict_planned(const cake_shape* shape, const float* const* indicator,
                        const void* plan, size_t plan_bytes, void* stream);
 
 /*
+ * b-bit storage of the retained cache (appendix "Comparison and compatibility with quantization
+ * methods", which combines eviction with a key-per-channel / value-per-token quantiser).
+ * Asymmetric uniform quantisation over groups of 32 of the keep[l, b] retained prefix rows of
+ * every head: keys per channel over 32 consecutive retained tokens, values per token over 32
+ * consecutive channels; zero = group minimum, scale = (max - min) / (2^bits - 1), code =
+ * round-half-to-even((x - zero) / scale), all in float32; a constant group has scale 0 and codes 0.
+ * x is recovered as zero + code * scale, within half a step.  The S_w window rows that follow the
+ * retained rows in k_hat / v_hat are left as they are (recent tokens stay in full precision).
+ *
+ *   bits       2, 4 or 8
+ *   k_hat, v_hat  tables; compacted [B, H_kv, >= keep + S_w, d] as written by cake_compact_kv,
+ *              element strides kv_strides (host [n_layers][3]), read only
+ *   keep       host [n_layers*B]: retained prefix rows (entry l*B + b); cap_l = max over b
+ *   k_codes, v_codes  tables; [B, H_kv, cap_l, d*bits/8] uint8, written: 8/bits consecutive
+ *              channels to a byte, the lower channel in the lower bits
+ *   k_scale, k_zero  tables; [B, H_kv, ceil(cap_l/32), d] f32, written (token group, channel)
+ *   v_scale, v_zero  tables; [B, H_kv, cap_l, d/32] f32, written (token, channel group)
+ * Rows at or beyond a sequence's own keep are neither read nor written.
+ */
+int cake_quantize_kv(const cake_shape* shape, int32_t bits,
+                     const void* const* k_hat, const void* const* v_hat, const int64_t* kv_strides,
+                     const int32_t* keep,
+                     uint8_t* const* k_codes, float* const* k_scale, float* const* k_zero,
+                     uint8_t* const* v_codes, float* const* v_scale, float* const* v_zero,
+                     void* stream);
+
+/*
  * Indicator maintenance for one generated token (implementation appendix, decoding branch of
  * the listing: the new query's attention over the cached keys outside the window is pooled and
  * the stored indicator is updated with it; Sec. 5, implementation details: eviction also runs

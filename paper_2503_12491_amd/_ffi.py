@@ -40,6 +40,8 @@ _SIGNATURES = {
                                              ctypes.c_size_t, _P, _P, _P]),
     "cake_keep_counts": (ctypes.c_int, [ctypes.POINTER(ctypes.c_int32), ctypes.POINTER(ctypes.c_int32), ctypes.c_int32,
                                         ctypes.c_int32, ctypes.POINTER(ctypes.c_int32)]),
+    "cake_quantize_kv": (ctypes.c_int, [ctypes.POINTER(cake_shape), ctypes.c_int32, _P, _P, ctypes.POINTER(ctypes.c_int64),
+                                        ctypes.POINTER(ctypes.c_int32), _P, _P, _P, _P, _P, _P, _P]),
     "cake_cascade_allocate": (ctypes.c_int, [ctypes.POINTER(ctypes.c_double), ctypes.c_int32, ctypes.c_int64,
                                              ctypes.c_int32, ctypes.c_int32, ctypes.POINTER(ctypes.c_int32)]),
     "cake_select_topk": (ctypes.c_int, [ctypes.POINTER(cake_shape), _P, ctypes.POINTER(ctypes.c_int32),

@@ -209,6 +209,14 @@ def cake_compact_kv(shape, k_in, v_in, kv_strides, cur_len, k, idx, ind_in, k_ou
                                   _stream(stream)))
 
 
+def cake_quantize_kv(shape, bits, k_hat, v_hat, kv_strides, keep, k_codes, k_scale, k_zero, v_codes, v_scale, v_zero,
+                     stream=None) -> None:
+    flat = [s for layer in kv_strides for s in layer]
+    _check(load().cake_quantize_kv(ctypes.byref(shape), bits, _ptr(k_hat), _ptr(v_hat), _i64(flat), _i32(keep),
+                                   _ptr(k_codes), _ptr(k_scale), _ptr(k_zero), _ptr(v_codes), _ptr(v_scale), _ptr(v_zero),
+                                   _stream(stream)))
+
+
 def cake_profile_enable(enable: bool) -> None:
     _check(load().cake_profile_enable(1 if enable else 0))
 

@@ -12,7 +12,8 @@ CSRC = os.path.join(PKG, "csrc")
 OBJ_DIR = os.path.join(ROOT, "_build")
 LIB_PATH = os.path.join(PKG, "libcake.so")
 
-SOURCES = ["cake_host.cpp", "window_scores.hip", "select_topk.hip", "compact_kv.hip", "decode_update.hip", "plan_evict.hip"]
+SOURCES = ["cake_host.cpp", "window_scores.hip", "select_topk.hip", "compact_kv.hip", "decode_update.hip", "plan_evict.hip",
+           "quantize_kv.hip"]
 # standalone issue-rate microbenchmark (not part of the library): `python -m paper_2503_12491_amd.build --microbench`
 MICROBENCH_SRC = os.path.join(CSRC, "microbench", "issue_port.hip")
 MICROBENCH_PATH = os.path.join(PKG, "issue_port_microbench")

@@ -428,6 +428,49 @@ class CascadeSession:
                           list(self.stage_budgets))
 
 
+@dataclass
+class QuantizedCache:
+    """Retained prefix rows of every layer in b-bit codes (cake_quantize_kv); per layer tensors."""
+    bits: int
+    k_codes: List[torch.Tensor]     # [B, H_kv, cap_l, d*bits/8] uint8
+    k_scale: List[torch.Tensor]     # [B, H_kv, ceil(cap_l/32), d] f32
+    k_zero: List[torch.Tensor]
+    v_codes: List[torch.Tensor]     # [B, H_kv, cap_l, d*bits/8] uint8
+    v_scale: List[torch.Tensor]     # [B, H_kv, cap_l, d/32] f32
+    v_zero: List[torch.Tensor]
+
+
+class CacheQuantizer:
+    """Buffers and the one call that store a pass's retained rows in 2, 4 or 8 bits."""
+
+    def __init__(self, result: PassResult, window: int, bits: int):
+        self.bits, self.S_w = int(bits), int(window)
+        self.keep = np.asarray(result.keep, dtype=np.int64)
+        self.L, self.B = self.keep.shape
+        k0 = result.k_out[0]
+        self.H_kv, self.d, dev = k0.shape[1], k0.shape[3], k0.device
+        self.k_hat, self.v_hat = result.k_out, result.v_out
+        self.shape = C.make_shape(self.B, self.L, self.H_kv, self.H_kv, self.d, self.S_w + 1, self.S_w, k0.dtype)
+        caps = [int(self.keep[l].max()) for l in range(self.L)]
+        mk = lambda shp, dt: [torch.empty(self.B, self.H_kv, *shp(c), dtype=dt, device=dev) for c in caps]
+        row_bytes = self.d * self.bits // 8
+        self.out = QuantizedCache(
+            self.bits,
+            mk(lambda c: (max(c, 1), row_bytes), torch.uint8), mk(lambda c: (max(-(-c // 32), 1), self.d), torch.float32),
+            mk(lambda c: (max(-(-c // 32), 1), self.d), torch.float32),
+            mk(lambda c: (max(c, 1), row_bytes), torch.uint8), mk(lambda c: (max(c, 1), self.d // 32), torch.float32),
+            mk(lambda c: (max(c, 1), self.d // 32), torch.float32))
+        self.tbl = [C.ptr_table(t) for t in (self.k_hat, self.v_hat, self.out.k_codes, self.out.k_scale, self.out.k_zero,
+                                             self.out.v_codes, self.out.v_scale, self.out.v_zero)]
+        self.strides = [_strides3(t) for t in self.k_hat]
+        self.keep_flat = [int(x) for x in self.keep.reshape(-1)]
+
+    def run(self, stream=None) -> QuantizedCache:
+        C.cake_quantize_kv(self.shape, self.bits, self.tbl[0], self.tbl[1], self.strides, self.keep_flat, *self.tbl[2:],
+                           stream)
+        return self.out
+
+
 class DecodeCache:
     """The evicted caches of a prompt during generation (implementation appendix, decoding branch):
     every layer stays at the budget the prefill pass gave it.  `step(layer, q_new, k_new, v_new)`
