@@ -293,7 +293,18 @@ int cake_compact_kv(const cake_shape* shape,
  *             infinite (the plan then holds the budgets of equal preferences), else 0
  *   k_in, v_in, indicator, kv_strides  as in cake_compact_kv / cake_select_topk, with one set of
  *             strides (host [3]) for all layers
+ *   compacted host [n_layers] or NULL (= all 0): 1 marks a layer whose k_in/v_in are themselves
+ *             outputs of an earlier cake_evict_planned, contiguous [B, H_kv, cap_cur[l] + S_w, d]
+ *             (cap_cur from this plan: the capacities are only known on the device); its strides
+ *             are derived from the plan instead of kv_strides.  This is what lets the stages of
+ *             the cascade (Alg. 1) follow one another without the host reading anything back.
+ *
+ * cake_plan_layout gives the byte offsets of the plan's ten parts for `shape` (n_layers, batch):
+ * budgets, keep, cur_len, cap_keep, cap_cur, copy_blocks, then the idx, k_out, v_out and ind_out
+ * tables, so that a caller can hand parts of one plan (keep counts, output tables) to the next call
+ * as device pointers.
  */
+int cake_plan_layout(const cake_shape* shape, size_t* offsets /* host [10], out */);
 int cake_plan_bytes(const cake_shape* shape, size_t* bytes /* host, out */);
 int cake_plan_eviction(const cake_shape* shape, const double* pref, int64_t total_budget,
                        const int32_t* cur_len,
@@ -301,6 +312,7 @@ int cake_plan_eviction(const cake_shape* shape, const double* pref, int64_t tota
                        void* plan, size_t plan_bytes, int32_t* status, void* stream);
 int cake_evict_planned(const cake_shape* shape, const float* const* indicator,
                        const void* const* k_in, const void* const* v_in, const int64_t* kv_strides,
+                       const uint8_t* compacted,
                        const void* plan, size_t plan_bytes, void* stream);
 
 /*

@@ -52,8 +52,9 @@ _SIGNATURES = {
     "cake_plan_bytes": (ctypes.c_int, [ctypes.POINTER(cake_shape), ctypes.POINTER(ctypes.c_size_t)]),
     "cake_plan_eviction": (ctypes.c_int, [ctypes.POINTER(cake_shape), _P, ctypes.c_int64, _P, _P, _P, _P, _P, _P,
                                           ctypes.c_size_t, _P, _P]),
-    "cake_evict_planned": (ctypes.c_int, [ctypes.POINTER(cake_shape), _P, _P, _P, ctypes.POINTER(ctypes.c_int64), _P,
-                                          ctypes.c_size_t, _P]),
+    "cake_evict_planned": (ctypes.c_int, [ctypes.POINTER(cake_shape), _P, _P, _P, ctypes.POINTER(ctypes.c_int64),
+                                          ctypes.POINTER(ctypes.c_uint8), _P, ctypes.c_size_t, _P]),
+    "cake_plan_layout": (ctypes.c_int, [ctypes.POINTER(cake_shape), ctypes.POINTER(ctypes.c_size_t)]),
     "cake_decode_update": (ctypes.c_int, [ctypes.POINTER(cake_shape), ctypes.POINTER(cake_params), _P,
                                           ctypes.POINTER(ctypes.c_int64), _P, ctypes.POINTER(ctypes.c_int64),
                                           ctypes.POINTER(ctypes.c_int32), _P, _P, ctypes.c_size_t, _P]),

@@ -154,9 +154,21 @@ def cake_plan_eviction(shape, pref, total_budget, cur_len, pool_idx, pool_k, poo
                                      plan.numel() * plan.element_size(), _ptr(status), _stream(stream)))
 
 
-def cake_evict_planned(shape, indicator, k_in, v_in, kv_strides, plan, stream=None) -> None:
-    _check(load().cake_evict_planned(ctypes.byref(shape), _ptr(indicator), _ptr(k_in), _ptr(v_in), _i64(kv_strides),
+def cake_evict_planned(shape, indicator, k_in, v_in, kv_strides, plan, stream=None, compacted=None) -> None:
+    """compacted: per layer 1 if its k_in/v_in are outputs of an earlier planned compaction (strides from the plan)."""
+    flags = None if compacted is None else (ctypes.c_uint8 * len(compacted))(*[int(x) for x in compacted])
+    _check(load().cake_evict_planned(ctypes.byref(shape), _ptr(indicator), _ptr(k_in), _ptr(v_in), _i64(kv_strides), flags,
                                      _ptr(plan), plan.numel() * plan.element_size(), _stream(stream)))
+
+
+PLAN_PARTS = ("budgets", "keep", "cur_len", "cap_keep", "cap_cur", "copy_blocks", "idx", "k_out", "v_out", "ind_out")
+
+
+def cake_plan_layout(shape: cake_shape) -> dict:
+    """Byte offsets of the plan's parts for (shape.n_layers, shape.batch), by name."""
+    out = (ctypes.c_size_t * 10)()
+    _check(load().cake_plan_layout(ctypes.byref(shape), out))
+    return dict(zip(PLAN_PARTS, [int(x) for x in out]))
 
 
 def plan_fields(plan_host, n_layers: int, batch: int):

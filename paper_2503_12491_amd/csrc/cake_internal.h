@@ -108,8 +108,10 @@ inline PlanView plan_view(const void* plan, int n_layers, int batch) {
 }
 // top-k and compaction of all layers with the counts and output places read from a plan
 int launch_topk_planned(const cake_shape* shape, const float* const* indicator, const PlanView& plan, hipStream_t stream);
+constexpr int kPlanMaskWords = 32;       // one bit per layer, n_layers <= 1024
 int launch_compact_planned(const cake_shape* shape, const void* const* k_in, const void* const* v_in,
-                           const int64_t* kv_strides, const float* const* ind_in, const PlanView& plan, hipStream_t stream);
+                           const int64_t* kv_strides, const uint8_t* compacted, const float* const* ind_in,
+                           const PlanView& plan, hipStream_t stream);
 
 // Layers [l0, l0+nl) that fit one launch under the two limits above.
 inline int launch_layers(int n_layers_left, int batch) {

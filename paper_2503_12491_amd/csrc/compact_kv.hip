@@ -35,7 +35,10 @@ struct CompactPlan {
   const int32_t* cap_keep;    // [L]
   const int32_t* copy_blocks; // [L*B + 1] running block counts (the work list)
   int32_t n_entries;          // L*B
-  int64_t s[3];
+  int64_t s[3];               // strides of the layers that come as the caller laid them out
+  // Bit l set: layer l's K and V are themselves outputs of an earlier planned compaction,
+  // contiguous [B, H_kv, cap_cur[l] + S_w, d]; their strides follow from the plan.
+  uint32_t compacted[kPlanMaskWords];
 };
 static_assert(kThreads * kUnroll == kCopyBlockPieces, "a workgroup step is one block of the plan's work list");
 constexpr int kListLds = 4096;       // work-list entries searched from LDS (longer lists are searched in memory)
@@ -84,8 +87,13 @@ __global__ __launch_bounds__(kThreads) void compact_kernel(CompactArgs a, Ragged
   const int keep = kPlanned ? plan.keep[ll * a.batch + b] : dims.keep[ll * a.batch + b];
   const int cap_cur = kPlanned ? plan.cap_cur[ll] : a.cap_cur[ll];
   const int cap_keep = kPlanned ? plan.cap_keep[ll] : a.cap_keep[ll];
-  const int64_t s0 = kPlanned ? plan.s[0] : st.s[ll][0], s1 = kPlanned ? plan.s[1] : st.s[ll][1],
-                s2 = kPlanned ? plan.s[2] : st.s[ll][2];
+  int64_t s0 = kPlanned ? plan.s[0] : st.s[ll][0], s1 = kPlanned ? plan.s[1] : st.s[ll][1],
+          s2 = kPlanned ? plan.s[2] : st.s[ll][2];
+  if (kPlanned && (plan.compacted[ll >> 5] >> (ll & 31) & 1u)) {
+    s2 = (int64_t)a.pieces * 16 / a.elem_bytes;
+    s1 = (int64_t)(cap_cur + a.window) * s2;
+    s0 = (int64_t)a.h_kv * s1;
+  }
   const int rows_out = keep + a.window;
   const int64_t total = (int64_t)rows_out * a.pieces;
 
@@ -142,8 +150,8 @@ __global__ __launch_bounds__(kThreads) void compact_kernel(CompactArgs a, Ragged
 }  // namespace cake
 
 int cake::launch_compact_planned(const cake_shape* shape, const void* const* k_in, const void* const* v_in,
-                                 const int64_t* kv_strides, const float* const* ind_in, const PlanView& plan,
-                                 hipStream_t stream) {
+                                 const int64_t* kv_strides, const uint8_t* compacted, const float* const* ind_in,
+                                 const PlanView& plan, hipStream_t stream) {
   const int eb = (int)elem_bytes(shape->dtype);
   CompactArgs a{};
   a.k_in = k_in; a.v_in = v_in;
@@ -155,7 +163,10 @@ int cake::launch_compact_planned(const cake_shape* shape, const void* const* k_i
   a.pieces = shape->head_dim * eb / 16;
   a.elem_bytes = eb;
   CompactPlan cp{plan.cur_len, plan.keep, plan.cap_cur, plan.cap_keep, plan.copy_blocks, shape->n_layers * shape->batch,
-                 {kv_strides[0], kv_strides[1], kv_strides[2]}};
+                 {kv_strides[0], kv_strides[1], kv_strides[2]}, {}};
+  if (compacted != nullptr)
+    for (int l = 0; l < shape->n_layers; ++l)
+      if (compacted[l]) cp.compacted[l >> 5] |= 1u << (l & 31);
   // 8192 workgroups in all (a few rounds of what the chip holds at once), striding over the work list
   const unsigned gx = (unsigned)std::max(1, 8192 / shape->n_kv_heads);
   hipLaunchKernelGGL(compact_kernel<true>, dim3(gx, shape->n_kv_heads), dim3(kThreads), 0,

@@ -280,8 +280,20 @@ extern "C" int cake_plan_eviction(const cake_shape* shape, const double* pref, i
   return CAKE_OK;
 }
 
+extern "C" int cake_plan_layout(const cake_shape* shape, size_t* offsets) {
+  CAKE_REQUIRE(offsets != nullptr, "offsets is NULL");
+  if (int rc = check_shape_basic(shape)) return rc;
+  const PlanLayout lay = plan_layout(shape->n_layers, shape->batch);
+  const size_t tbl = (size_t)shape->n_layers * sizeof(void*);
+  const size_t all[10] = {lay.off_budgets, lay.off_keep, lay.off_cur, lay.off_cap_keep, lay.off_cap_cur, lay.off_blocks,
+                          lay.off_tables, lay.off_tables + tbl, lay.off_tables + 2 * tbl, lay.off_tables + 3 * tbl};
+  for (int i = 0; i < 10; ++i) offsets[i] = all[i];
+  return CAKE_OK;
+}
+
 extern "C" int cake_evict_planned(const cake_shape* shape, const float* const* indicator,
                                   const void* const* k_in, const void* const* v_in, const int64_t* kv_strides,
+                                  const uint8_t* compacted,
                                   const void* plan, size_t plan_bytes, void* stream) {
   if (int rc = check_shape_basic(shape)) return rc;
   CAKE_REQUIRE(indicator && k_in && v_in && kv_strides && plan, "a pointer argument is NULL");
@@ -297,5 +309,5 @@ extern "C" int cake_evict_planned(const cake_shape* shape, const float* const* i
   const PlanView view = plan_view(plan, shape->n_layers, shape->batch);
   hipStream_t st = static_cast<hipStream_t>(stream);
   if (int rc = launch_topk_planned(shape, indicator, view, st)) return rc;
-  return launch_compact_planned(shape, k_in, v_in, kv_strides, indicator, view, st);
+  return launch_compact_planned(shape, k_in, v_in, kv_strides, compacted, indicator, view, st);
 }

@@ -428,6 +428,107 @@ class CascadeSession:
                           list(self.stage_budgets))
 
 
+class DeviceCascade:
+    """Alg. 1 for one sequence with nothing read back between the stages: `admit` scores layer m,
+    the budgets B^(m) of the layers seen so far are computed on the device (cake_plan_eviction
+    over m + 1 layers with the previous stage's keep counts as current lengths), and every layer is
+    re-evicted from its previous compacted cache into the other of two output pools
+    (cake_evict_planned with the earlier layers flagged as compacted).  The output tables and keep
+    counts of one stage's plan are handed to the next stage as device data.  Layers admitted while
+    everything still fits are copied whole.  Same caches and budgets as CascadeSession (tested);
+    original positions are not tracked.  The host waits once, in `result`."""
+
+    def __init__(self, n_layers: int, total_budget: int, params=None):
+        self.L, self.total_budget = int(n_layers), int(total_budget)
+        self.params = params if params is not None else C.make_params()
+        self.m = 0
+        self._geom = None
+
+    def _setup(self, q_win, k):
+        B, H_q, S_w, d = q_win.shape
+        assert B == 1, "DeviceCascade handles one sequence (use CascadeSession for batches)"
+        H_kv, N = k.shape[1], k.shape[2]
+        dev, dt = k.device, k.dtype
+        self._geom = (H_q, H_kv, S_w, d, N, dt, dev)
+        L = self.L
+        self.shape1 = C.make_shape(1, 1, H_q, H_kv, d, N, S_w, dt)
+        self.ws1 = torch.empty(C.cake_workspace_bytes(self.shape1), dtype=torch.uint8, device=dev)
+        self.pref = torch.zeros(L, dtype=torch.float64, device=dev)          # [B = 1, L]
+        self.hv = torch.zeros(L, 2, dtype=torch.float64, device=dev)
+        self.cur = torch.full((L,), N - S_w, dtype=torch.int32, device=dev)  # current evictable lengths
+        self.status = torch.zeros(1, dtype=torch.int32, device=dev)
+        self.shapes = [C.make_shape(1, m + 1, H_q, H_kv, d, N, S_w, dt) for m in range(L)]
+        self.plans = [torch.zeros(C.cake_plan_bytes(self.shapes[-1]), dtype=torch.uint8, device=dev) for _ in range(2)]
+        # every stage's outputs hold at most min(total_budget, (m + 1) N) rows per head, windows included
+        rows = min(self.total_budget, L * N)
+        self.pools = [dict(k=torch.empty(H_kv * rows * d, dtype=dt, device=dev), v=torch.empty(H_kv * rows * d, dtype=dt, device=dev),
+                           idx=torch.empty(H_kv * rows, dtype=torch.int32, device=dev),
+                           ind=torch.empty(H_kv * rows, dtype=torch.float32, device=dev)) for _ in range(2)]
+        self.tbl_q = torch.zeros(1, dtype=torch.int64, device=dev)
+        self.tbl_k1 = torch.zeros(1, dtype=torch.int64, device=dev)
+        self.tbl_ind1 = torch.zeros(1, dtype=torch.int64, device=dev)
+        self.in_k = torch.zeros(L, dtype=torch.int64, device=dev)            # current K / V / indicator of every layer
+        self.in_v = torch.zeros(L, dtype=torch.int64, device=dev)
+        self.in_ind = torch.zeros(L, dtype=torch.int64, device=dev)
+        self.alive = []                                                       # keeps the layers of the running stage referenced
+
+    def _part(self, plan: torch.Tensor, shape, name: str, dtype, count: int) -> torch.Tensor:
+        off = C.cake_plan_layout(shape)[name]
+        size = torch.empty(0, dtype=dtype).element_size()
+        return plan[off: off + count * size].view(dtype)
+
+    def admit(self, q_win: torch.Tensor, k: torch.Tensor, v: torch.Tensor, indicator_out: Optional[torch.Tensor] = None) -> None:
+        assert self.m < self.L, "every layer has been admitted"
+        if self._geom is None:
+            self._setup(q_win, k)
+        H_q, H_kv, S_w, d, N, dt, dev = self._geom
+        assert tuple(q_win.shape) == (1, H_q, S_w, d) and tuple(k.shape) == (1, H_kv, N, d) and v.shape == k.shape
+        assert _strides3(v) == _strides3(k)
+        m = self.m
+        ind = indicator_out if indicator_out is not None else torch.empty(1, H_kv, N - S_w, dtype=torch.float32, device=dev)
+        self.alive = [q_win, k, v, ind] + self.alive[:4]                     # this stage's and the previous stage's inputs
+        self.tbl_q.fill_(q_win.data_ptr()); self.tbl_k1.fill_(k.data_ptr()); self.tbl_ind1.fill_(ind.data_ptr())
+        C.cake_window_scores(self.shape1, self.params, self.tbl_q, self.tbl_k1, _strides3(q_win), _strides3(k), self.tbl_ind1,
+                             self.ws1)
+        C.cake_layer_preference(self.shape1, self.params, self.ws1, self.pref[m: m + 1], self.hv[m: m + 1])
+        self.in_k[m: m + 1].fill_(k.data_ptr()); self.in_v[m: m + 1].fill_(v.data_ptr()); self.in_ind[m: m + 1].fill_(ind.data_ptr())
+        shape, plan, pool = self.shapes[m], self.plans[m & 1], self.pools[m & 1]
+        C.cake_plan_eviction(shape, self.pref, self.total_budget, self.cur, pool["idx"], pool["k"], pool["v"], pool["ind"],
+                             plan, self.status)
+        C.cake_evict_planned(shape, self.in_ind, self.in_k, self.in_v, _strides3(k), plan, compacted=[1] * m + [0])
+        # the next stage starts from this stage's outputs
+        n = m + 1
+        self.in_k[:n].copy_(self._part(plan, shape, "k_out", torch.int64, n))
+        self.in_v[:n].copy_(self._part(plan, shape, "v_out", torch.int64, n))
+        self.in_ind[:n].copy_(self._part(plan, shape, "ind_out", torch.int64, n))
+        self.cur[:n].copy_(self._part(plan, shape, "keep", torch.int32, n))
+        self.m = n
+
+    def result(self) -> PassResult:
+        """Budgets, keep counts and the final caches (views into the last stage's pool)."""
+        torch.cuda.synchronize()
+        H_q, H_kv, S_w, d, N, dt, dev = self._geom
+        m = self.m
+        shape, plan, pool = self.shapes[m - 1], self.plans[(m - 1) & 1], self.pools[(m - 1) & 1]
+        if int(self.status.item()) != 0:
+            raise C.CakeError(-1, "a layer preference is NaN, negative or infinite")
+        budgets, keep, _, _ = C.plan_fields(plan.cpu(), m, 1)
+        caps = keep.max(axis=1).astype(np.int64)
+        k_out, v_out, ind_out, idx = [], [], [], []
+        o_kv = o_i = 0
+        for l in range(m):
+            c = int(caps[l])
+            n_kv, n_i = H_kv * (c + S_w) * d, H_kv * c
+            k_out.append(pool["k"][o_kv: o_kv + n_kv].view(1, H_kv, c + S_w, d))
+            v_out.append(pool["v"][o_kv: o_kv + n_kv].view(1, H_kv, c + S_w, d))
+            ind_out.append(pool["ind"][o_i: o_i + n_i].view(1, H_kv, c))
+            idx.append(None)
+            o_kv += n_kv
+            o_i += n_i
+        return PassResult(budgets, keep, self.pref[:m].cpu().numpy()[None], self.hv[:m].cpu().numpy()[None], [], idx, k_out,
+                          v_out, ind_out)
+
+
 @dataclass
 class QuantizedCache:
     """Retained prefix rows of every layer in b-bit codes (cake_quantize_kv); per layer tensors."""

@@ -118,3 +118,38 @@ def test_cascade_with_handed_over_row_lse_equals_one_shot(cake):
         n_k = int(shot.keep[l, 0])
         assert torch.equal(casc.idx[l][0, :, :n_k], shot_idx[l][0, :, :n_k])
         assert torch.equal(casc.k_out[l][0, :, : n_k + cfg.window], shot_k[l][0, :, : n_k + cfg.window])
+
+
+@pytest.mark.parametrize("name", ["tiny", "llama_reduced", "window64", "everything_fits_at_first"])
+def test_device_cascade_equals_host_cascade_and_one_shot(cake, name):
+    """DeviceCascade (stages chained on the device: plan over the layers seen so far, earlier layers
+    re-evicted from their compacted caches with strides taken from the plan) against the host-driven
+    CascadeSession stage by stage in the end result, and against the one-shot pass (Thm. 2)."""
+    cfg = {"tiny": CONFIGS[1],
+           "llama_reduced": CONFIGS[2].scaled(n_layers=6, seq_len=2048 + 32 + 9, total_budget=6 * 300),
+           "window64": CONFIGS[4].scaled(n_layers=5, seq_len=4096 + 64 + 3, total_budget=5 * 500),
+           "everything_fits_at_first": CONFIGS[2].scaled(n_layers=6, seq_len=700, total_budget=2 * 700 + 333)}[name]
+    say(f"device cascade {name}")
+    inp = make_config_inputs(cfg, device=DEV)
+    L = cfg.n_layers
+    q = [inp["q_win"][l] for l in range(L)]
+    k = [inp["k"][l] for l in range(L)]
+    v = [inp["v"][l] for l in range(L)]
+    host = cake.CascadeSession(L, cfg.total_budget, track_positions=False)
+    dev = cake.DeviceCascade(L, cfg.total_budget)
+    for l in range(L):
+        host.admit(q[l], k[l], v[l])
+        dev.admit(q[l], k[l], v[l])
+    want, got = host.result(), dev.result()
+    shot = cake.EvictionPass(q, k, v, cfg.total_budget).run()
+    torch.cuda.synchronize()
+    assert np.array_equal(got.budgets, want.budgets) and np.array_equal(got.keep, want.keep)
+    assert np.array_equal(got.budgets, shot.budgets)
+    np.testing.assert_array_equal(got.pref, want.pref)
+    for l in range(L):
+        n_k = int(want.keep[l, 0])
+        for a, b, c in ((got.k_out, want.k_out, shot.k_out), (got.v_out, want.v_out, shot.v_out)):
+            assert torch.equal(a[l][0, :, : n_k + cfg.window], b[l][0, :, : n_k + cfg.window]), (l, "vs host cascade")
+            assert torch.equal(a[l][0, :, : n_k + cfg.window], c[l][0, :, : n_k + cfg.window]), (l, "vs one-shot")
+        assert torch.equal(got.ind_out[l][0, :, :n_k], want.ind_out[l][0, :, :n_k])
+        assert torch.equal(got.ind_out[l][0, :, :n_k], shot.ind_out[l][0, :, :n_k])
