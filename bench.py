@@ -244,7 +244,7 @@ def main():
                                        "frac": (read_b + write_b) / (ms * 1e-3) / 1e9 / HBM_PEAK_GBPS, "traffic": None}}))
         return
     if args.cascade:
-        on_device = B == 1 and not args.host_allocation      # stages chained on the device (one sequence)
+        on_device = not args.host_allocation                 # stages chained on the device
 
         def one_cascade():
             if not on_device:

@@ -429,9 +429,9 @@ class CascadeSession:
 
 
 class DeviceCascade:
-    """Alg. 1 for one sequence with nothing read back between the stages: `admit` scores layer m,
-    the budgets B^(m) of the layers seen so far are computed on the device (cake_plan_eviction
-    over m + 1 layers with the previous stage's keep counts as current lengths), and every layer is
+    """Alg. 1 with nothing read back between the stages: `admit` scores layer m, the budgets
+    B^(m) of the layers seen so far are computed on the device (cake_plan_eviction over m + 1
+    layers with the previous stage's keep counts as current lengths), and every layer is
     re-evicted from its previous compacted cache into the other of two output pools
     (cake_evict_planned with the earlier layers flagged as compacted).  The output tables and keep
     counts of one stage's plan are handed to the next stage as device data.  Layers admitted while
@@ -446,34 +446,38 @@ class DeviceCascade:
 
     def _setup(self, q_win, k):
         B, H_q, S_w, d = q_win.shape
-        assert B == 1, "DeviceCascade handles one sequence (use CascadeSession for batches)"
         H_kv, N = k.shape[1], k.shape[2]
         dev, dt = k.device, k.dtype
-        self._geom = (H_q, H_kv, S_w, d, N, dt, dev)
+        self._geom = (B, H_q, H_kv, S_w, d, N, dt, dev)
         L = self.L
-        self.shape1 = C.make_shape(1, 1, H_q, H_kv, d, N, S_w, dt)
+        self.shape1 = C.make_shape(B, 1, H_q, H_kv, d, N, S_w, dt)
         self.ws1 = torch.empty(C.cake_workspace_bytes(self.shape1), dtype=torch.uint8, device=dev)
-        self.pref = torch.zeros(L, dtype=torch.float64, device=dev)          # [B = 1, L]
-        self.hv = torch.zeros(L, 2, dtype=torch.float64, device=dev)
-        self.cur = torch.full((L,), N - S_w, dtype=torch.int32, device=dev)  # current evictable lengths
-        self.status = torch.zeros(1, dtype=torch.int32, device=dev)
-        self.shapes = [C.make_shape(1, m + 1, H_q, H_kv, d, N, S_w, dt) for m in range(L)]
+        self.pref_all = torch.zeros(B, L, dtype=torch.float64, device=dev)    # every layer's preference, [B, L]
+        self.hv_all = torch.zeros(B, L, 2, dtype=torch.float64, device=dev)
+        self.pref1 = torch.zeros(B, dtype=torch.float64, device=dev)          # the admitted layer's, [B, 1]
+        self.hv1 = torch.zeros(B, 2, dtype=torch.float64, device=dev)
+        self.pref_stage = torch.zeros(B * L, dtype=torch.float64, device=dev) # [B, m + 1] contiguous for the plan
+        self.cur = torch.full((L, B), N - S_w, dtype=torch.int32, device=dev) # current evictable lengths
+        self.status = torch.zeros(B, dtype=torch.int32, device=dev)
+        self.shapes = [C.make_shape(B, m + 1, H_q, H_kv, d, N, S_w, dt) for m in range(L)]
+        self.layouts = [C.cake_plan_layout(sh) for sh in self.shapes]
         self.plans = [torch.zeros(C.cake_plan_bytes(self.shapes[-1]), dtype=torch.uint8, device=dev) for _ in range(2)]
-        # every stage's outputs hold at most min(total_budget, (m + 1) N) rows per head, windows included
-        rows = min(self.total_budget, L * N)
-        self.pools = [dict(k=torch.empty(H_kv * rows * d, dtype=dt, device=dev), v=torch.empty(H_kv * rows * d, dtype=dt, device=dev),
-                           idx=torch.empty(H_kv * rows, dtype=torch.int32, device=dev),
-                           ind=torch.empty(H_kv * rows, dtype=torch.float32, device=dev)) for _ in range(2)]
-        self.tbl_q = torch.zeros(1, dtype=torch.int64, device=dev)
-        self.tbl_k1 = torch.zeros(1, dtype=torch.int64, device=dev)
-        self.tbl_ind1 = torch.zeros(1, dtype=torch.int64, device=dev)
-        self.in_k = torch.zeros(L, dtype=torch.int64, device=dev)            # current K / V / indicator of every layer
-        self.in_v = torch.zeros(L, dtype=torch.int64, device=dev)
-        self.in_ind = torch.zeros(L, dtype=torch.int64, device=dev)
-        self.alive = []                                                       # keeps the layers of the running stage referenced
+        # A stage's outputs: layer l holds [B, H_kv, cap_l + S_w, d] with cap_l = max_b keep, and
+        # sum_l (keep[l, b] + S_w) <= min(total_budget, (m + 1) N) for every sequence b
+        rows = B * min(self.total_budget, L * N)
+        bh = B * H_kv
+        self.pools = [dict(k=torch.empty(bh * rows * d, dtype=dt, device=dev), v=torch.empty(bh * rows * d, dtype=dt, device=dev),
+                           idx=torch.empty(bh * rows, dtype=torch.int32, device=dev),
+                           ind=torch.empty(bh * rows, dtype=torch.float32, device=dev)) for _ in range(2)]
+        # one pinned row per stage: the host never waits for the device here, so a staging row must
+        # not be written again while its upload may still be pending
+        self.new_host = torch.zeros(L, 6, dtype=torch.int64).pin_memory()
+        self.new_ptrs = torch.zeros(6, dtype=torch.int64, device=dev)         # q, k, indicator tables of the scores; k, v, ind of the layer
+        self.inputs = torch.zeros(4, L, dtype=torch.int64, device=dev)        # rows: (unused), K, V, indicator tables of all layers
+        self.alive = []
 
-    def _part(self, plan: torch.Tensor, shape, name: str, dtype, count: int) -> torch.Tensor:
-        off = C.cake_plan_layout(shape)[name]
+    def _part(self, plan: torch.Tensor, m: int, name: str, dtype, count: int) -> torch.Tensor:
+        off = self.layouts[m][name]
         size = torch.empty(0, dtype=dtype).element_size()
         return plan[off: off + count * size].view(dtype)
 
@@ -481,51 +485,56 @@ class DeviceCascade:
         assert self.m < self.L, "every layer has been admitted"
         if self._geom is None:
             self._setup(q_win, k)
-        H_q, H_kv, S_w, d, N, dt, dev = self._geom
-        assert tuple(q_win.shape) == (1, H_q, S_w, d) and tuple(k.shape) == (1, H_kv, N, d) and v.shape == k.shape
+        B, H_q, H_kv, S_w, d, N, dt, dev = self._geom
+        assert tuple(q_win.shape) == (B, H_q, S_w, d) and tuple(k.shape) == (B, H_kv, N, d) and v.shape == k.shape
         assert _strides3(v) == _strides3(k)
-        m = self.m
-        ind = indicator_out if indicator_out is not None else torch.empty(1, H_kv, N - S_w, dtype=torch.float32, device=dev)
+        m, n = self.m, self.m + 1
+        ind = indicator_out if indicator_out is not None else torch.empty(B, H_kv, N - S_w, dtype=torch.float32, device=dev)
         self.alive = [q_win, k, v, ind] + self.alive[:4]                     # this stage's and the previous stage's inputs
-        self.tbl_q.fill_(q_win.data_ptr()); self.tbl_k1.fill_(k.data_ptr()); self.tbl_ind1.fill_(ind.data_ptr())
-        C.cake_window_scores(self.shape1, self.params, self.tbl_q, self.tbl_k1, _strides3(q_win), _strides3(k), self.tbl_ind1,
-                             self.ws1)
-        C.cake_layer_preference(self.shape1, self.params, self.ws1, self.pref[m: m + 1], self.hv[m: m + 1])
-        self.in_k[m: m + 1].fill_(k.data_ptr()); self.in_v[m: m + 1].fill_(v.data_ptr()); self.in_ind[m: m + 1].fill_(ind.data_ptr())
+        host = self.new_host[m]
+        host.numpy()[:] = (q_win.data_ptr(), k.data_ptr(), ind.data_ptr(), k.data_ptr(), v.data_ptr(), ind.data_ptr())
+        self.new_ptrs.copy_(host, non_blocking=True)
+        self.inputs[1:4, m].copy_(self.new_ptrs[3:6])
+        C.cake_window_scores(self.shape1, self.params, self.new_ptrs[0:1], self.new_ptrs[1:2], _strides3(q_win), _strides3(k),
+                             self.new_ptrs[2:3], self.ws1)
+        C.cake_layer_preference(self.shape1, self.params, self.ws1, self.pref1, self.hv1)
+        self.pref_all[:, m].copy_(self.pref1)
+        self.hv_all[:, m].copy_(self.hv1)
+        stage_pref = self.pref_stage[: B * n].view(B, n)
+        stage_pref.copy_(self.pref_all[:, :n])
         shape, plan, pool = self.shapes[m], self.plans[m & 1], self.pools[m & 1]
-        C.cake_plan_eviction(shape, self.pref, self.total_budget, self.cur, pool["idx"], pool["k"], pool["v"], pool["ind"],
+        C.cake_plan_eviction(shape, stage_pref, self.total_budget, self.cur, pool["idx"], pool["k"], pool["v"], pool["ind"],
                              plan, self.status)
-        C.cake_evict_planned(shape, self.in_ind, self.in_k, self.in_v, _strides3(k), plan, compacted=[1] * m + [0])
-        # the next stage starts from this stage's outputs
-        n = m + 1
-        self.in_k[:n].copy_(self._part(plan, shape, "k_out", torch.int64, n))
-        self.in_v[:n].copy_(self._part(plan, shape, "v_out", torch.int64, n))
-        self.in_ind[:n].copy_(self._part(plan, shape, "ind_out", torch.int64, n))
-        self.cur[:n].copy_(self._part(plan, shape, "keep", torch.int32, n))
+        C.cake_evict_planned(shape, self.inputs[3], self.inputs[1], self.inputs[2], _strides3(k), plan,
+                             compacted=[1] * m + [0])
+        # the next stage starts from this stage's outputs: its four tables sit one after the other in the plan
+        self.inputs[:, :n].copy_(self._part(plan, m, "idx", torch.int64, 4 * n).view(4, n))
+        self.cur[:n].copy_(self._part(plan, m, "keep", torch.int32, n * B).view(n, B))
         self.m = n
 
     def result(self) -> PassResult:
         """Budgets, keep counts and the final caches (views into the last stage's pool)."""
         torch.cuda.synchronize()
-        H_q, H_kv, S_w, d, N, dt, dev = self._geom
+        B, H_q, H_kv, S_w, d, N, dt, dev = self._geom
         m = self.m
-        shape, plan, pool = self.shapes[m - 1], self.plans[(m - 1) & 1], self.pools[(m - 1) & 1]
-        if int(self.status.item()) != 0:
+        plan, pool = self.plans[(m - 1) & 1], self.pools[(m - 1) & 1]
+        if int(self.status.max().item()) != 0:
             raise C.CakeError(-1, "a layer preference is NaN, negative or infinite")
-        budgets, keep, _, _ = C.plan_fields(plan.cpu(), m, 1)
+        budgets, keep, _, _ = C.plan_fields(plan.cpu(), m, B)
         caps = keep.max(axis=1).astype(np.int64)
         k_out, v_out, ind_out, idx = [], [], [], []
         o_kv = o_i = 0
+        bh = B * H_kv
         for l in range(m):
             c = int(caps[l])
-            n_kv, n_i = H_kv * (c + S_w) * d, H_kv * c
-            k_out.append(pool["k"][o_kv: o_kv + n_kv].view(1, H_kv, c + S_w, d))
-            v_out.append(pool["v"][o_kv: o_kv + n_kv].view(1, H_kv, c + S_w, d))
-            ind_out.append(pool["ind"][o_i: o_i + n_i].view(1, H_kv, c))
+            n_kv, n_i = bh * (c + S_w) * d, bh * c
+            k_out.append(pool["k"][o_kv: o_kv + n_kv].view(B, H_kv, c + S_w, d))
+            v_out.append(pool["v"][o_kv: o_kv + n_kv].view(B, H_kv, c + S_w, d))
+            ind_out.append(pool["ind"][o_i: o_i + n_i].view(B, H_kv, c))
             idx.append(None)
             o_kv += n_kv
             o_i += n_i
-        return PassResult(budgets, keep, self.pref[:m].cpu().numpy()[None], self.hv[:m].cpu().numpy()[None], [], idx, k_out,
+        return PassResult(budgets, keep, self.pref_all[:, :m].cpu().numpy(), self.hv_all[:, :m].cpu().numpy(), [], idx, k_out,
                           v_out, ind_out)
 
 

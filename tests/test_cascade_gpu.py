@@ -120,7 +120,7 @@ def test_cascade_with_handed_over_row_lse_equals_one_shot(cake):
         assert torch.equal(casc.k_out[l][0, :, : n_k + cfg.window], shot_k[l][0, :, : n_k + cfg.window])
 
 
-@pytest.mark.parametrize("name", ["tiny", "llama_reduced", "window64", "everything_fits_at_first"])
+@pytest.mark.parametrize("name", ["tiny", "llama_reduced", "window64", "everything_fits_at_first", "batch3_group5"])
 def test_device_cascade_equals_host_cascade_and_one_shot(cake, name):
     """DeviceCascade (stages chained on the device: plan over the layers seen so far, earlier layers
     re-evicted from their compacted caches with strides taken from the plan) against the host-driven
@@ -128,7 +128,8 @@ def test_device_cascade_equals_host_cascade_and_one_shot(cake, name):
     cfg = {"tiny": CONFIGS[1],
            "llama_reduced": CONFIGS[2].scaled(n_layers=6, seq_len=2048 + 32 + 9, total_budget=6 * 300),
            "window64": CONFIGS[4].scaled(n_layers=5, seq_len=4096 + 64 + 3, total_budget=5 * 500),
-           "everything_fits_at_first": CONFIGS[2].scaled(n_layers=6, seq_len=700, total_budget=2 * 700 + 333)}[name]
+           "everything_fits_at_first": CONFIGS[2].scaled(n_layers=6, seq_len=700, total_budget=2 * 700 + 333),
+           "batch3_group5": CONFIGS[5].scaled(n_layers=4, batch=3, seq_len=1300, total_budget=4 * 200)}[name]
     say(f"device cascade {name}")
     inp = make_config_inputs(cfg, device=DEV)
     L = cfg.n_layers
@@ -147,9 +148,10 @@ def test_device_cascade_equals_host_cascade_and_one_shot(cake, name):
     assert np.array_equal(got.budgets, shot.budgets)
     np.testing.assert_array_equal(got.pref, want.pref)
     for l in range(L):
-        n_k = int(want.keep[l, 0])
-        for a, b, c in ((got.k_out, want.k_out, shot.k_out), (got.v_out, want.v_out, shot.v_out)):
-            assert torch.equal(a[l][0, :, : n_k + cfg.window], b[l][0, :, : n_k + cfg.window]), (l, "vs host cascade")
-            assert torch.equal(a[l][0, :, : n_k + cfg.window], c[l][0, :, : n_k + cfg.window]), (l, "vs one-shot")
-        assert torch.equal(got.ind_out[l][0, :, :n_k], want.ind_out[l][0, :, :n_k])
-        assert torch.equal(got.ind_out[l][0, :, :n_k], shot.ind_out[l][0, :, :n_k])
+        for s_ in range(cfg.batch):
+            n_k = int(want.keep[l, s_])
+            for a, b, c in ((got.k_out, want.k_out, shot.k_out), (got.v_out, want.v_out, shot.v_out)):
+                assert torch.equal(a[l][s_, :, : n_k + cfg.window], b[l][s_, :, : n_k + cfg.window]), (l, s_, "vs host cascade")
+                assert torch.equal(a[l][s_, :, : n_k + cfg.window], c[l][s_, :, : n_k + cfg.window]), (l, s_, "vs one-shot")
+            assert torch.equal(got.ind_out[l][s_, :, :n_k], want.ind_out[l][s_, :, :n_k])
+            assert torch.equal(got.ind_out[l][s_, :, :n_k], shot.ind_out[l][s_, :, :n_k])
