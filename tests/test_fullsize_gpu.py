@@ -56,7 +56,7 @@ def _check_sampled(cake, cfg, slices, pref_layers, indicator_slices=()):
     # always include the slice with the largest budget, so that selection and compaction are
     # exercised on thousands of rows whatever the preferences turn out to be
     l_big, b_big = np.unravel_index(int(np.argmax(res.keep)), res.keep.shape)
-    slices = list(slices) + [(int(l_big), int(b_big), 2)]
+    slices = list(slices) + [(int(l_big), int(b_big), min(2, cfg.n_kv_heads - 1))]
     for (l, b, g) in slices:
         say(f"  slice l={l} b={b} g={g}")
         o = oracle_slice(q[l, b], k[l, b], g, G, params)
@@ -135,3 +135,12 @@ def test_config2_full_cascade_equals_one_shot(cake):
         n_k = int(shot.keep[l, 0])
         assert torch.equal(casc.idx[l][0, :, :n_k], shot_idx[l][0, :, :n_k])
         assert torch.equal(casc.k_out[l][0, :, : n_k + S_w], shot_k[l][0, :, : n_k + S_w])
+
+
+def test_half_a_million_keys(cake):
+    """Four times the benchmark's context: N = 524288, S_w = 64, one layer, two KV heads of four
+    query heads (offsets beyond 2^27 elements per slice, 256 chunks per slice); one slice against
+    the oracle, the other by the properties that hold at any size."""
+    say("full size: N = 524288")
+    cfg = CONFIGS[4].scaled(n_layers=1, n_q_heads=8, n_kv_heads=2, seq_len=524288, total_budget=4096)
+    _check_sampled(cake, cfg, slices=[(0, 0, 1)], pref_layers=[])
