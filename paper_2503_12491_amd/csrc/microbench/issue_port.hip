@@ -3,9 +3,10 @@
 // kernels spend their time on exactly this mix (logits on the matrix pipe; scaling, exponentials
 // and sums on the vector pipe), so these figures give the bound their durations are compared to.
 //
-// Every test runs 4 workgroups per compute unit of 4 (or 8) waves, i.e. one (two) wave(s) per SIMD
-// at a time, with register-only loops; the figure printed is nanoseconds per instruction (or per
-// MFMA with its K vector instructions) per SIMD.  Standalone program: prints a table, returns 0.
+// Every test runs register-only loops in workgroups of 4 or 8 waves (wave i of a workgroup runs on
+// SIMD i % 4), one or four workgroups per compute unit, so 1, 2, 4 or 8 waves share a SIMD; the
+// figure printed is nanoseconds per instruction (or per MFMA with its K vector instructions) per
+// SIMD.  Standalone program: prints a table, returns 0.
 #include <hip/hip_runtime.h>
 
 #include <cstdio>
@@ -27,7 +28,8 @@ enum Mode { kFma, kExp, kMfma32, kMfma16, kSplitWaves };
 
 // kFma / kExp: 128 independent-enough instructions per iteration (8 chains).
 // kMfma32 / kMfma16: 16 MFMAs per iteration (4 accumulator chains), each followed by K v_fma_f32.
-// kSplitWaves: odd waves run the 16 MFMAs, even waves 16*K v_fma_f32 (two waves per SIMD).
+// kSplitWaves: waves 4-7 of a workgroup run the 16 MFMAs, waves 0-3 run 16*K v_fma_f32, so every
+// SIMD holds one wave of each kind per workgroup.
 template <int MODE, int K>
 __global__ __launch_bounds__(512) void issue_loop(float* out, int iters, float seed) {
   float v[8];
@@ -39,8 +41,8 @@ __global__ __launch_bounds__(512) void issue_loop(float* out, int iters, float s
     a[i] = (__bf16)(seed * 0.01f);
     b[i] = (__bf16)(seed * 0.02f);
   }
-  const bool mfma_wave = MODE != kSplitWaves || ((threadIdx.x >> 6) & 1);
-  const bool fma_wave = MODE != kSplitWaves || !((threadIdx.x >> 6) & 1);
+  const bool mfma_wave = MODE != kSplitWaves || ((threadIdx.x >> 8) & 1);
+  const bool fma_wave = MODE != kSplitWaves || !((threadIdx.x >> 8) & 1);
   for (int it = 0; it < iters; ++it) {
     if (MODE == kFma || MODE == kExp) {
 #pragma unroll
@@ -76,8 +78,9 @@ __global__ __launch_bounds__(512) void issue_loop(float* out, int iters, float s
 }
 
 template <int MODE, int K>
-int run(const char* name, int threads, double per_iter, const char* unit, float* out, int waves_per_unit = 1) {
-  const int iters = 2000, blocks = 256 * 4;
+int run(const char* name, int threads, double per_iter, const char* unit, float* out, int waves_per_unit = 1,
+        int blocks_per_cu = 4) {
+  const int iters = 2000 * 4 / blocks_per_cu, blocks = 256 * blocks_per_cu;
   hipEvent_t e0, e1;
   CHECK(hipEventCreate(&e0));
   CHECK(hipEventCreate(&e1));
@@ -102,22 +105,34 @@ int main() {
   float* out;
   CHECK(hipMalloc(&out, 256 * 4 * 512 * sizeof(float)));
   int rc = 0;
-  rc |= run<kFma, 0>("v_fma_f32, 1 wave/SIMD", 256, 128, "instruction", out);
-  rc |= run<kFma, 0>("v_fma_f32, 2 waves/SIMD", 512, 128, "instruction", out);
-  rc |= run<kExp, 0>("v_exp_f32, 1 wave/SIMD", 256, 128, "instruction", out);
-  rc |= run<kExp, 0>("v_exp_f32, 2 waves/SIMD", 512, 128, "instruction", out);
-  rc |= run<kMfma32, 0>("mfma 32x32x16 bf16 alone", 256, 16, "MFMA", out);
-  rc |= run<kMfma32, 4>("mfma 32x32x16 bf16 + 4 fma each", 256, 16, "MFMA", out);
-  rc |= run<kMfma32, 6>("mfma 32x32x16 bf16 + 6 fma each", 256, 16, "MFMA", out);
-  rc |= run<kMfma32, 8>("mfma 32x32x16 bf16 + 8 fma each", 256, 16, "MFMA", out);
-  rc |= run<kMfma32, 12>("mfma 32x32x16 bf16 + 12 fma each", 256, 16, "MFMA", out);
-  rc |= run<kMfma32, 16>("mfma 32x32x16 bf16 + 16 fma each", 256, 16, "MFMA", out);
-  rc |= run<kMfma16, 0>("mfma 16x16x32 bf16 alone", 256, 16, "MFMA", out);
-  rc |= run<kMfma16, 4>("mfma 16x16x32 bf16 + 4 fma each", 256, 16, "MFMA", out);
-  rc |= run<kMfma16, 8>("mfma 16x16x32 bf16 + 8 fma each", 256, 16, "MFMA", out);
-  rc |= run<kMfma16, 16>("mfma 16x16x32 bf16 + 16 fma each", 256, 16, "MFMA", out);
-  rc |= run<kSplitWaves, 8>("2 waves/SIMD: 16 mfma 32x32x16 | 128 fma", 512, 16, "MFMA (+8 fma in the other wave)", out, 2);
-  rc |= run<kSplitWaves, 16>("2 waves/SIMD: 16 mfma 32x32x16 | 256 fma", 512, 16, "MFMA (+16 fma in the other wave)", out, 2);
+  rc |= run<kFma, 0>("v_fma_f32, 1 wave/SIMD", 256, 128, "instruction", out, 1, 1);
+  rc |= run<kFma, 0>("v_fma_f32, 2 waves/SIMD", 512, 128, "instruction", out, 1, 1);
+  rc |= run<kFma, 0>("v_fma_f32, 4 waves/SIMD", 256, 128, "instruction", out);
+  rc |= run<kFma, 0>("v_fma_f32, 8 waves/SIMD", 512, 128, "instruction", out);
+  rc |= run<kExp, 0>("v_exp_f32, 1 wave/SIMD", 256, 128, "instruction", out, 1, 1);
+  rc |= run<kExp, 0>("v_exp_f32, 4 waves/SIMD", 256, 128, "instruction", out);
+  rc |= run<kMfma32, 0>("mfma 32x32x16 bf16 alone, 1 wave/SIMD", 256, 16, "MFMA", out, 1, 1);
+  rc |= run<kMfma32, 0>("mfma 32x32x16 bf16 alone, 4 waves/SIMD", 256, 16, "MFMA", out);
+  rc |= run<kMfma32, 4>("mfma 32x32x16 bf16 + 4 fma each, 4 waves/SIMD", 256, 16, "MFMA", out);
+  rc |= run<kMfma32, 6>("mfma 32x32x16 bf16 + 6 fma each, 4 waves/SIMD", 256, 16, "MFMA", out);
+  rc |= run<kMfma32, 8>("mfma 32x32x16 bf16 + 8 fma each, 4 waves/SIMD", 256, 16, "MFMA", out);
+  rc |= run<kMfma32, 12>("mfma 32x32x16 bf16 + 12 fma each, 4 waves/SIMD", 256, 16, "MFMA", out);
+  rc |= run<kMfma32, 16>("mfma 32x32x16 bf16 + 16 fma each, 4 waves/SIMD", 256, 16, "MFMA", out);
+  rc |= run<kMfma32, 8>("mfma 32x32x16 bf16 + 8 fma each, 1 wave/SIMD", 256, 16, "MFMA", out, 1, 1);
+  rc |= run<kMfma32, 16>("mfma 32x32x16 bf16 + 16 fma each, 1 wave/SIMD", 256, 16, "MFMA", out, 1, 1);
+  rc |= run<kMfma32, 8>("mfma 32x32x16 bf16 + 8 fma each, 2 waves/SIMD", 512, 16, "MFMA", out, 1, 1);
+  rc |= run<kMfma32, 12>("mfma 32x32x16 bf16 + 12 fma each, 2 waves/SIMD", 512, 16, "MFMA", out, 1, 1);
+  rc |= run<kMfma32, 16>("mfma 32x32x16 bf16 + 16 fma each, 2 waves/SIMD", 512, 16, "MFMA", out, 1, 1);
+  rc |= run<kMfma32, 8>("mfma 32x32x16 bf16 + 8 fma each, 8 waves/SIMD", 512, 16, "MFMA", out);
+  rc |= run<kMfma32, 16>("mfma 32x32x16 bf16 + 16 fma each, 8 waves/SIMD", 512, 16, "MFMA", out);
+  rc |= run<kMfma16, 0>("mfma 16x16x32 bf16 alone, 4 waves/SIMD", 256, 16, "MFMA", out);
+  rc |= run<kMfma16, 4>("mfma 16x16x32 bf16 + 4 fma each, 4 waves/SIMD", 256, 16, "MFMA", out);
+  rc |= run<kMfma16, 8>("mfma 16x16x32 bf16 + 8 fma each, 4 waves/SIMD", 256, 16, "MFMA", out);
+  rc |= run<kMfma16, 16>("mfma 16x16x32 bf16 + 16 fma each, 4 waves/SIMD", 256, 16, "MFMA", out);
+  rc |= run<kSplitWaves, 8>("1+1 waves/SIMD: 16 mfma 32x32x16 | 128 fma", 512, 16, "MFMA (+8 fma in the other wave)", out, 2, 1);
+  rc |= run<kSplitWaves, 16>("1+1 waves/SIMD: 16 mfma 32x32x16 | 256 fma", 512, 16, "MFMA (+16 fma in the other wave)", out, 2, 1);
+  rc |= run<kSplitWaves, 8>("4+4 waves/SIMD: 16 mfma 32x32x16 | 128 fma", 512, 16, "MFMA (+8 fma in the other wave)", out, 2);
+  rc |= run<kSplitWaves, 16>("4+4 waves/SIMD: 16 mfma 32x32x16 | 256 fma", 512, 16, "MFMA (+16 fma in the other wave)", out, 2);
   CHECK(hipFree(out));
   return rc;
 }
