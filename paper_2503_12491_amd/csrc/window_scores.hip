@@ -215,27 +215,25 @@ __device__ __forceinline__ void pass1_sums(const f32x16 (&acc)[MB], int kb, floa
   for (int nb = 0; nb < MB; ++nb) {
     const int last_visible = min(n_p + nb * 32 + c32, n - 1);
     auto hidden = [&](int v) { return kTail && kb + 8 * (v / 4) + 4 * hh + (v % 4) > last_visible; };
-    float bsum[2] = {0.f, 0.f};           // two chains: consecutive additions do not wait on each other
+    float bsum[2];                        // two chains: consecutive additions do not wait on each other
 #pragma unroll
     for (int v = 0; v < 16; ++v) {
-      const float e = fast_exp2(fmaf(acc[nb][v], cv, -mref[nb]));
-      bsum[v & 1] += hidden(v) ? 0.f : e;
+      const float e = hidden(v) ? 0.f : fast_exp2(fmaf(acc[nb][v], cv, -mref[nb]));
+      if (v < 2) bsum[v] = e;
+      else bsum[v & 1] += e;
     }
     float block = bsum[0] + bsum[1];
     // Sixteen terms of at most 2^40 each add at most 2^44.  Anything above that (or inf/NaN)
     // means a logit outran the row's reference: redo the block with a reference of its own.
-    const bool lift = !(block <= 16.f * 1.0995116e12f);
-    if (__builtin_amdgcn_ballot_w64(lift)) {
-      if (lift) {
-        float rmax = kMasked;
+    if (!(block <= 16.f * 1.0995116e12f)) {
+      float rmax = kMasked;
 #pragma unroll
-        for (int v = 0; v < 16; ++v) rmax = fmaxf(rmax, hidden(v) ? kMasked : acc[nb][v] * cv);
-        lsum[nb] *= fast_exp2(mref[nb] - rmax);
-        mref[nb] = rmax;
-        block = 0.f;
+      for (int v = 0; v < 16; ++v) rmax = fmaxf(rmax, hidden(v) ? kMasked : acc[nb][v] * cv);
+      lsum[nb] *= fast_exp2(mref[nb] - rmax);
+      mref[nb] = rmax;
+      block = 0.f;
 #pragma unroll
-        for (int v = 0; v < 16; ++v) block += hidden(v) ? 0.f : fast_exp2(acc[nb][v] * cv - rmax);
-      }
+      for (int v = 0; v < 16; ++v) block += hidden(v) ? 0.f : fast_exp2(acc[nb][v] * cv - rmax);
     }
     lsum[nb] += block;
   }
