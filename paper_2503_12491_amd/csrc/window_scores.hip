@@ -639,24 +639,76 @@ __global__ __launch_bounds__(kPack ? 1024 : 512) void scores_pass2(ScoreArgs a) 
 // so that every un-pooled value is read from memory once.
 constexpr int kPoolSpan = 2048;
 constexpr int kPoolMaxHalf = 64;        // widest supported pooling window: 2*64+1
+constexpr int kPoolQuadHalf = 4;        // widest half window of the four-outputs-per-lane path
+
+// Four consecutive outputs from the twelve staged values around them (w[4..7] are the outputs' own
+// positions).
+template <int kHalf>
+__device__ __forceinline__ float4 pool_quad(const float (&w)[12]) {
+  float o[4];
+#pragma unroll
+  for (int k = 0; k < 4; ++k) {
+    float m = w[4 + k];
+#pragma unroll
+    for (int d = 1; d <= kHalf; ++d) m = fmaxf(m, fmaxf(w[4 + k - d], w[4 + k + d]));
+    o[k] = m;
+  }
+  return make_float4(o[0], o[1], o[2], o[3]);
+}
+
 __global__ __launch_bounds__(256) void pool_indicator(ScoreArgs a) {
-  __shared__ float win[kPoolSpan + 2 * kPoolMaxHalf];
+  // position j0 + i of the span sits at win[kPoolMaxHalf + i]
+  __shared__ __attribute__((aligned(16))) float win[kPoolSpan + 2 * kPoolMaxHalf];
   const int slice = blockIdx.y;
   int l, b, g;
   slice_coords(a, slice, l, b, g);
   const int half = a.pool / 2;
   const int j0 = blockIdx.x * kPoolSpan;
+  const int span = min(kPoolSpan, a.n_p - j0);
   const float* raw = a.raw + (int64_t)slice * a.n_p;
-  const int lo = j0 - half, count = min(kPoolSpan, a.n_p - j0) + 2 * half;
-  for (int i = threadIdx.x; i < count; i += 256) {
-    const int j = lo + i;
-    win[i] = (j >= 0 && j < a.n_p) ? raw[j] : -INFINITY;     // clipped edges never win the max
+  float* out = a.indicator[l] + ((int64_t)b * a.h_kv + g) * a.n_p;
+  // Rows of a multiple of four positions at 16-byte aligned addresses, windows of at most nine:
+  // 16-byte loads and stores, four outputs per lane from three 16-byte LDS reads.
+  const bool quads = a.n_p % 4 == 0 && half <= kPoolQuadHalf &&
+                     ((reinterpret_cast<uintptr_t>(raw) | reinterpret_cast<uintptr_t>(out)) & 15) == 0;
+  if (quads) {
+    const float4* raw4 = reinterpret_cast<const float4*>(raw + j0);
+    for (int q = threadIdx.x; q < span / 4; q += 256)
+      *reinterpret_cast<float4*>(&win[kPoolMaxHalf + 4 * q]) = raw4[q];
+    if (threadIdx.x < 8) {            // four positions on either side; clipped edges never win the max
+      const int i = threadIdx.x < 4 ? (int)threadIdx.x - 4 : span + (int)threadIdx.x - 4;
+      const int j = j0 + i;
+      win[kPoolMaxHalf + i] = (j >= 0 && j < a.n_p) ? raw[j] : -INFINITY;
+    }
+    __syncthreads();
+    float4* out4 = reinterpret_cast<float4*>(out + j0);
+    for (int q = threadIdx.x; q < span / 4; q += 256) {
+      float w[12];
+#pragma unroll
+      for (int v = 0; v < 3; ++v) {
+        const float4 x = *reinterpret_cast<const float4*>(&win[kPoolMaxHalf + 4 * q - 4 + 4 * v]);
+        w[4 * v] = x.x; w[4 * v + 1] = x.y; w[4 * v + 2] = x.z; w[4 * v + 3] = x.w;
+      }
+      float4 r;
+      switch (half) {
+        case 0: r = pool_quad<0>(w); break;
+        case 1: r = pool_quad<1>(w); break;
+        case 2: r = pool_quad<2>(w); break;
+        case 3: r = pool_quad<3>(w); break;
+        default: r = pool_quad<4>(w); break;
+      }
+      out4[q] = r;
+    }
+    return;
+  }
+  for (int i = (int)threadIdx.x - half; i < span + half; i += 256) {
+    const int j = j0 + i;
+    win[kPoolMaxHalf + i] = (j >= 0 && j < a.n_p) ? raw[j] : -INFINITY;     // clipped edges never win the max
   }
   __syncthreads();
-  float* out = a.indicator[l] + ((int64_t)b * a.h_kv + g) * a.n_p;
-  for (int i = threadIdx.x; i < kPoolSpan && j0 + i < a.n_p; i += 256) {
-    float m = win[i];
-    for (int k = 1; k <= 2 * half; ++k) m = fmaxf(m, win[i + k]);
+  for (int i = threadIdx.x; i < span; i += 256) {
+    float m = win[kPoolMaxHalf + i];
+    for (int k = 1; k <= half; ++k) m = fmaxf(m, fmaxf(win[kPoolMaxHalf + i - k], win[kPoolMaxHalf + i + k]));
     out[j0 + i] = m;
   }
 }

@@ -207,6 +207,16 @@ def test_scores_parameter_variants(cake):
     _check_scores(cake, cfg)
 
 
+def test_scores_pooling_widths_and_row_alignment(cake):
+    # the pooling kernel has a 16-byte path (rows of a multiple of four positions, windows up to nine)
+    # and a general one; both, on prefixes longer than one pooling span, edges included
+    say("scores pooling widths")
+    for seq_len in (2048 + 32 + 2072, 2048 + 32 + 2071):          # prefix 4120 (multiple of four) and 4119
+        cfg = CONFIGS[2].scaled(n_layers=1, seq_len=seq_len, total_budget=512, n_q_heads=4, n_kv_heads=2)
+        for pool in (1, 5, 9, 11, 129):
+            _check_scores(cake, cfg, cake.make_params(pool_kernel=pool))
+
+
 def test_scores_with_handed_over_row_lse(cake):
     # single pass over K with the normalisers supplied: against the oracle fed the same f32 values,
     # and against the library's own two-pass result
