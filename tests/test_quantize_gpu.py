@@ -77,6 +77,43 @@ def test_quantised_cache_equals_the_oracle_ragged_batch_and_fp32(cake):
     _check(cake, CONFIGS[1], 2)
 
 
+def test_quantiser_rounding_boundaries(cake):
+    # Every group holds 0 and 2^b - 1, so its scale is exactly 1 and the quotients are the values
+    # themselves: exact ties k + 1/2 (round-half-even) and their nearest representable neighbours,
+    # where a product with a rounded reciprocal could fall on the other side of the boundary.
+    from types import SimpleNamespace
+    say("quantise: values on and next to the rounding boundaries")
+    rng = np.random.default_rng(7)
+    for bits, dtype in ((4, torch.bfloat16), (8, torch.bfloat16), (2, torch.float32), (8, torch.float32)):
+        levels, d, rows, window, H = 2 ** bits - 1, 128, 70, 32, 2
+        top = min(levels, 127)                                        # k + 1/2 is a bf16 number up to 127.5
+        def tile():
+            x = torch.from_numpy(rng.integers(0, top, size=(H, rows, d)).astype(np.float32) + 0.5).to(dtype)
+            step = torch.from_numpy(rng.choice([-1, 0, 0, 1], size=(H, rows, d)))      # units in the last place of dtype
+            as_int = torch.int16 if dtype == torch.bfloat16 else torch.int32
+            x = (x.view(as_int) + step.to(as_int)).view(dtype)                          # positive values: the neighbouring numbers
+            return x.float().numpy()                                                    # what the device will hold
+        k, v = tile(), tile()
+        k[:, 0::32] = 0.0; k[:, 1::32] = levels                       # per channel, in every token group
+        v[:, :, 0::32] = 0.0; v[:, :, 1::32] = levels                 # per token, in every channel group
+        pad = np.zeros((H, window, d), np.float32)
+        to_dev = lambda x: torch.from_numpy(np.concatenate([x, pad], axis=1)[None]).to(dtype).to(DEV)
+        res = SimpleNamespace(keep=np.array([[rows]]), k_out=[to_dev(k)], v_out=[to_dev(v)])
+        out = cake.CacheQuantizer(res, window, bits).run()
+        torch.cuda.synchronize()
+        ties = 0
+        for g in range(H):
+            (kc, ks, kz), (vc, vs, vz) = co.quantize_cache(k[g], v[g], bits)
+            assert np.all(ks == 1.0) and np.all(vs == 1.0) and np.all(kz == 0.0) and np.all(vz == 0.0)
+            np.testing.assert_array_equal(_unpack(out.k_codes[0][0, g, :rows].cpu().numpy(), bits), kc)
+            np.testing.assert_array_equal(_unpack(out.v_codes[0][0, g, :rows].cpu().numpy(), bits), vc)
+            np.testing.assert_array_equal(out.k_scale[0][0, g, :3].cpu().numpy(), ks)
+            np.testing.assert_array_equal(out.v_zero[0][0, g, :rows].cpu().numpy(), vz)
+            ties += int(np.sum(k[g] - np.floor(k[g]) == 0.5)) + int(np.sum(v[g] - np.floor(v[g]) == 0.5))
+        assert ties > 1000
+        say(f"  {bits}-bit {dtype}: {ties} exact ties among {2 * H * rows * d} values")
+
+
 def test_quantiser_rejects_bad_arguments(cake):
     from paper_2503_12491_amd import binding as C
     cfg = CONFIGS[1]
