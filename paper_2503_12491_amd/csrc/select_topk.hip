@@ -16,8 +16,8 @@ namespace {
 
 constexpr int kThreads = 1024;
 constexpr int kWaves = kThreads / 64;
-constexpr int kBatch = 4;                           // 16-byte loads in flight per thread in the histogram sweeps
-constexpr int kSlotsPerThread = 2;                  // consecutive 4-entry slots per thread in the ordered sweep
+constexpr int kBatch = 8;                           // 16-byte loads in flight per thread in the histogram sweeps
+constexpr int kSlotsPerThread = 4;                  // consecutive 4-entry slots per thread in the ordered sweep
 constexpr int kTileSlots = kThreads * kSlotsPerThread;
 constexpr int kMaxBins = 2048;
 constexpr int kCopies = 4;                          // histogram copies, chosen by lane: fewer lanes meet on one LDS address
