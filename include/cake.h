@@ -333,7 +333,9 @@ int cake_evict_planned(const cake_shape* shape, const float* const* indicator,
  *              channels to a byte, the lower channel in the lower bits
  *   k_scale, k_zero  tables; [B, H_kv, ceil(cap_l/32), d] f32, written (token group, channel)
  *   v_scale, v_zero  tables; [B, H_kv, cap_l, d/32] f32, written (token, channel group)
- * Rows at or beyond a sequence's own keep are neither read nor written.
+ * Rows at or beyond a sequence's own keep are neither read nor written.  The arrays behind k_hat and
+ * v_hat start at 16-byte boundaries (strides are checked to be multiples of 16 bytes), the code
+ * arrays at 8-byte boundaries; the tables live in device memory, so the addresses are not checked.
  */
 int cake_quantize_kv(const cake_shape* shape, int32_t bits,
                      const void* const* k_hat, const void* const* v_hat, const int64_t* kv_strides,
