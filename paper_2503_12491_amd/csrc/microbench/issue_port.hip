@@ -24,9 +24,10 @@ typedef float f32x4 __attribute__((ext_vector_type(4)));
     }                                                                              \
   } while (0)
 
-enum Mode { kFma, kExp, kMfma32, kMfma16, kSplitWaves };
+enum Mode { kFma, kExp, kExpFma, kMfma32, kMfma16, kSplitWaves };
 
 // kFma / kExp: 128 independent-enough instructions per iteration (8 chains).
+// kExpFma: 32 groups per iteration of one v_exp_f32 followed by K v_fma_f32 on other registers.
 // kMfma32 / kMfma16: 16 MFMAs per iteration (4 accumulator chains), each followed by K v_fma_f32.
 // kSplitWaves: waves 4-7 of a workgroup run the 16 MFMAs, waves 0-3 run 16*K v_fma_f32, so every
 // SIMD holds one wave of each kind per workgroup.
@@ -44,7 +45,14 @@ __global__ __launch_bounds__(512) void issue_loop(float* out, int iters, float s
   const bool mfma_wave = MODE != kSplitWaves || ((threadIdx.x >> 8) & 1);
   const bool fma_wave = MODE != kSplitWaves || !((threadIdx.x >> 8) & 1);
   for (int it = 0; it < iters; ++it) {
-    if (MODE == kFma || MODE == kExp) {
+    if (MODE == kExpFma) {
+#pragma unroll
+      for (int r = 0; r < 32; ++r) {
+        asm volatile("v_exp_f32 %0, %0" : "+v"(small[r & 3][r >> 3]));
+#pragma unroll
+        for (int i = 0; i < K; ++i) asm volatile("v_fma_f32 %0, %0, %1, %0" : "+v"(v[(r * K + i) & 7]) : "v"(seed));
+      }
+    } else if (MODE == kFma || MODE == kExp) {
 #pragma unroll
       for (int r = 0; r < 16; ++r)
 #pragma unroll
@@ -111,6 +119,8 @@ int main() {
   rc |= run<kFma, 0>("v_fma_f32, 8 waves/SIMD", 512, 128, "instruction", out);
   rc |= run<kExp, 0>("v_exp_f32, 1 wave/SIMD", 256, 128, "instruction", out, 1, 1);
   rc |= run<kExp, 0>("v_exp_f32, 4 waves/SIMD", 256, 128, "instruction", out);
+  rc |= run<kExpFma, 2>("v_exp_f32 + 2 v_fma_f32, 4 waves/SIMD", 256, 32, "group", out);
+  rc |= run<kExpFma, 4>("v_exp_f32 + 4 v_fma_f32, 4 waves/SIMD", 256, 32, "group", out);
   rc |= run<kMfma32, 0>("mfma 32x32x16 bf16 alone, 1 wave/SIMD", 256, 16, "MFMA", out, 1, 1);
   rc |= run<kMfma32, 0>("mfma 32x32x16 bf16 alone, 4 waves/SIMD", 256, 16, "MFMA", out);
   rc |= run<kMfma32, 4>("mfma 32x32x16 bf16 + 4 fma each, 4 waves/SIMD", 256, 16, "MFMA", out);
